@@ -1,0 +1,129 @@
+/* saps.h — C ABI of the MI355X (gfx950) library for one SAPS-PSGD round.
+ *
+ * The library holds the models of all n workers as one n x ld fp32 matrix in the HBM
+ * of one GPU (row i = worker i, the paper's column x^(i) of X, Sec. III) and performs
+ * the per-round numeric work of Alg. 2 (worker side) on all rows at once:
+ *
+ *   local step      Alg. 2 line 5 / procedure SGD:  x <- x - gamma * grad
+ *                   (with an optional heavy-ball momentum buffer v, which the paper
+ *                   does not have: v <- mu*v + g ; x <- x - lr*v)
+ *   random mask     Sec. II-B, Eq. (3): m[j] = 1 with probability 1/c, the same on all
+ *                   workers because every worker derives it from the round's seed
+ *   sparsify        Eq. (2): x~ = x o m; only the non-zeros travel (packed, ascending j)
+ *   exchange+merge  Alg. 2 lines 8-10 with GenerateW's weights (1/2, 1/2): masked
+ *                   coordinates of two matched workers become the mean of the two,
+ *                   all other coordinates keep their value (Eq. (6))
+ *
+ * The mask is never stored.  Coordinate j of round t is kept iff
+ *     Philox4x32-10(key = (lo32 seed, hi32 seed),
+ *                   ctr = (lo32(j>>2), hi32(j>>2), lo32 t, hi32 t))[j & 3]  <  floor(2^32 / c_s)
+ * where s is the segment that contains j (64-bit compare; c_s = 1 keeps everything).
+ *
+ * Conventions
+ *   - X, G, V, msg, idx, K_dev are DEVICE pointers owned by the caller, 16-byte aligned;
+ *     the library keeps none of them after a call returns.  peer, seg_off, seg_c are HOST
+ *     pointers, copied during the call.
+ *   - X, G, V share the row stride ld (floats), ld >= N, ld % 4 == 0.  Columns [N, ld) are
+ *     never read or written.  msg has row stride msg_ld (the capacity given at creation).
+ *   - All work is enqueued on the HIP stream given to saps_create(); calls return without
+ *     waiting for the GPU.  Calls on one context must not overlap from several threads.
+ *   - K (number of kept coordinates of the round) is known only on the device.  If K exceeds
+ *     the capacity msg_ld the round's kernels write NOTHING to X, V, msg, idx (K_dev is
+ *     still written) and a sticky flag is raised that saps_poll_status() reports.
+ *   - Host-detectable errors are returned immediately and nothing is enqueued.
+ *   - X, G, V, msg, idx must not alias.
+ *   - Limits: 1 <= n <= 65535, 0 <= N <= 0xFFFF0000, n_seg >= 1.
+ */
+#ifndef SAPS_H
+#define SAPS_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct saps_ctx saps_ctx; /* opaque; owns private device scratch only */
+
+typedef enum {
+    SAPS_OK = 0,
+    SAPS_EINVAL = 1,    /* null / misaligned pointer, bad size, ld < N, ld % 4, bad segments, c < 1 */
+    SAPS_EMATCH = 2,    /* peer[] out of range or not an involution                              */
+    SAPS_ECAPACITY = 3, /* K > msg_ld: the round was skipped on the device (see saps_poll_status) */
+    SAPS_EHIP = 4       /* a HIP runtime call failed; text in saps_last_error()                   */
+} saps_status;
+
+/* Shape of the model matrix and of the per-segment compression ratios (Sec. II-B uses one
+ * c for the whole model: n_seg = 1).  seg_off has n_seg+1 non-decreasing entries with
+ * seg_off[0] = 0 and seg_off[n_seg] = N; seg_c[s] >= 1 is the ratio c of segment s. */
+typedef struct {
+    int32_t n;             /* workers (rows)                         */
+    int64_t N;             /* coordinates per model                  */
+    int64_t ld;            /* row stride of X, G, V in floats        */
+    int32_t n_seg;         /* number of segments                     */
+    const int64_t* seg_off; /* HOST, n_seg + 1 entries               */
+    const double* seg_c;    /* HOST, n_seg entries                   */
+} saps_layout;
+
+/* Creates a context for one layout.  msg_ld = capacity of a packed message row (floats,
+ * multiple of 4, >= 0).  hip_stream = hipStream_t to enqueue on (NULL = default stream).
+ * Allocates the private scratch (about 4 bytes per 1024 coordinates + 4*msg_ld + 16*n). */
+saps_status saps_create(saps_ctx** out, const saps_layout* layout, int64_t msg_ld, void* hip_stream);
+saps_status saps_destroy(saps_ctx* ctx);
+
+/* Local step of Alg. 2 line 5 on every row:  v = fma(mu, v, g); x = fma(-lr, v, x)
+ * (two correctly rounded fp32 fused multiply-adds).  V == NULL is allowed iff mu == 0 and
+ * gives the paper's plain x = fma(-lr, g, x).  X and V are updated in place. */
+saps_status saps_sgd_step(saps_ctx* ctx, float* X, const float* G, float* V, float lr, float mu);
+
+/* Eq. (3) + Eq. (2): generates the round's mask, writes the ascending list of kept
+ * coordinates idx[0..K), the packed rows msg[i*msg_ld + k] = X[i*ld + idx[k]] and *K_dev = K.
+ * X is read only.  K_dev is a device int64. */
+saps_status saps_mask_compact(saps_ctx* ctx, const float* X, uint64_t seed, uint64_t round,
+                              uint32_t* idx, float* msg, int64_t* K_dev);
+
+/* Alg. 2 line 10 (averaging) for the matching peer[] (HOST, n entries, peer[peer[i]] == i;
+ * peer[i] == i leaves row i untouched):  X[i*ld + idx[k]] = (msg[i][k] + msg[peer[i]][k]) * 0.5f
+ * for k < *K_dev.  idx, msg, K_dev as written by saps_mask_compact. */
+saps_status saps_merge(saps_ctx* ctx, float* X, const int32_t* peer, const uint32_t* idx,
+                       const float* msg, const int64_t* K_dev);
+
+/* One whole round in Alg. 2 order, bit-identical to
+ *   saps_sgd_step; saps_mask_compact; saps_merge
+ * but with every element of X, G, V read once and X, V written once.  G == NULL skips the
+ * local step (exchange-only round; V, lr, mu ignored).  idx, msg, K_dev may each be NULL
+ * when the caller does not need that output. */
+saps_status saps_round(saps_ctx* ctx, float* X, const float* G, float* V, float lr, float mu,
+                       uint64_t seed, uint64_t round, const int32_t* peer,
+                       uint32_t* idx, float* msg, int64_t* K_dev);
+
+/* Waits for the context's stream, returns SAPS_ECAPACITY if any call since the last poll
+ * was skipped for K > msg_ld (and clears that flag), else SAPS_OK.  If K_host != NULL it
+ * receives the K of the most recent mask generation. */
+saps_status saps_poll_status(saps_ctx* ctx, int64_t* K_host);
+
+/* Text of the last host-side error on this context (never NULL). */
+const char* saps_last_error(const saps_ctx* ctx);
+
+/* Launch-shape knobs for measurement sweeps; results never depend on them.
+ * Unknown knob or out-of-range value: SAPS_EINVAL. */
+enum {
+    SAPS_TUNE_PAIRS_PER_BLOCK = 0, /* fused round: matched pairs handled per workgroup: 1, 2, 4, 8, 16 */
+    SAPS_TUNE_XCD_REMAP = 1,       /* fused round: 0 = tiles in launch order, 1 = contiguous tile range per XCD */
+    SAPS_TUNE_NONTEMPORAL = 2,     /* fused round and local step: 0 = plain, 1 = non-temporal loads/stores */
+    SAPS_TUNE_EXCHANGE_PATH = 3    /* exchange-only round: 0 = by expected density, 1 = index list, 2 = tile walk */
+};
+saps_status saps_set_tuning(saps_ctx* ctx, int32_t knob, int32_t value);
+
+/* Plain device-to-device streaming copy of `count` floats (16-byte aligned, count % 4 == 0)
+ * with the same access shape as the round kernels: the bandwidth yardstick of the
+ * benchmark and the scale reference for profiler byte counters.  Not part of the method. */
+saps_status saps_stream_copy(saps_ctx* ctx, float* dst, const float* src, int64_t count);
+
+/* Library ABI version (bumped when a signature changes). */
+int32_t saps_abi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SAPS_H */

@@ -1,0 +1,373 @@
+// Host side of the C ABI declared in include/saps.h: argument checks, the private scratch
+// of a context, and the launch sequences of the SAPS-PSGD round (Alg. 2 lines 5-10).
+#include "saps_device.hpp"
+
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/saps.h"
+
+using namespace saps;
+
+namespace {
+
+constexpr int RING = 4;                 // pinned staging slots for the matching
+constexpr int64_t MAX_N = 0xFFFF0000ll;
+constexpr int32_t MAX_WORKERS = 65535;
+constexpr uint32_t LIST_GRID_X_MAX = 1024;
+
+struct Slot {
+    int32_t* host = nullptr;            // pinned: peer[n] followed by units[2n]
+    hipEvent_t done = nullptr;
+    bool used = false;
+};
+
+}  // namespace
+
+struct saps_ctx {
+    int32_t n = 0;
+    int64_t N = 0, ld = 0, msg_ld = 0;
+    hipStream_t stream = nullptr;
+    uint32_t ntiles = 0;
+    // mask description (segments with equal thresholds merged, empty ones dropped)
+    int32_t n_seg = 1;
+    uint64_t T0 = 0;
+    double density = 0.0;               // expected K / N
+    uint32_t* d_seg_end = nullptr;
+    uint64_t* d_seg_T = nullptr;
+    // scratch
+    uint32_t* d_tile = nullptr;         // ntiles + 1 counts / exclusive bases
+    int64_t* d_K = nullptr;             // K of the most recent mask generation
+    int32_t* d_flag = nullptr;          // sticky capacity flag
+    uint32_t* d_idx = nullptr;          // msg_ld entries, used when the caller passes idx == NULL
+    int32_t* d_match = nullptr;         // peer[n] followed by units[2n]
+    Slot ring[RING];
+    uint64_t calls = 0;
+    // launch-shape knobs
+    int32_t ppb = 4, xcd_remap = 0, nontemporal = 0, exchange_path = 0;
+    std::string err;
+};
+
+namespace {
+
+saps_status fail(saps_ctx* c, saps_status s, const char* what) {
+    if (c) c->err = what;
+    return s;
+}
+
+saps_status hip_fail(saps_ctx* c, hipError_t e, const char* where) {
+    if (c) {
+        c->err = std::string(where) + ": " + hipGetErrorString(e);
+    }
+    return SAPS_EHIP;
+}
+
+#define SAPS_HIP(ctx, call)                                        \
+    do {                                                           \
+        hipError_t e__ = (call);                                   \
+        if (e__ != hipSuccess) return hip_fail((ctx), e__, #call); \
+    } while (0)
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+MaskParams mask_params(const saps_ctx* c, uint64_t seed, uint64_t round) {
+    MaskParams P;
+    P.key0 = (uint32_t)seed; P.key1 = (uint32_t)(seed >> 32);
+    P.rnd0 = (uint32_t)round; P.rnd1 = (uint32_t)(round >> 32);
+    P.N = (uint32_t)c->N;
+    P.n_seg = c->n_seg;
+    P.T0 = c->T0;
+    P.seg_end = c->d_seg_end;
+    P.seg_T = c->d_seg_T;
+    return P;
+}
+
+// peer[] must be an involution of [0, n).
+bool matching_ok(int32_t n, const int32_t* peer) {
+    for (int32_t i = 0; i < n; ++i) {
+        const int32_t p = peer[i];
+        if (p < 0 || p >= n) return false;
+        if (peer[p] != i) return false;
+    }
+    return true;
+}
+
+// Stages peer[] and the unit list (pairs i < p, singles i == p) through a pinned slot and
+// enqueues the upload.  Returns the number of units.
+saps_status upload_matching(saps_ctx* c, const int32_t* peer, int32_t* n_units) {
+    Slot& s = c->ring[c->calls++ % RING];
+    if (s.used) SAPS_HIP(c, hipEventSynchronize(s.done));
+    int32_t* h = s.host;
+    std::memcpy(h, peer, sizeof(int32_t) * c->n);
+    int32_t* units = h + c->n;
+    int32_t u = 0;
+    for (int32_t i = 0; i < c->n; ++i) {
+        if (peer[i] >= i) { units[2 * u] = i; units[2 * u + 1] = peer[i]; ++u; }
+    }
+    *n_units = u;
+    SAPS_HIP(c, hipMemcpyAsync(c->d_match, h, sizeof(int32_t) * (size_t)(c->n + 2 * u), hipMemcpyHostToDevice, c->stream));
+    SAPS_HIP(c, hipEventRecord(s.done, c->stream));
+    s.used = true;
+    return SAPS_OK;
+}
+
+// K1 + K2: per-tile counts, exclusive tile bases, K and the capacity flag.
+saps_status enqueue_count_scan(saps_ctx* c, const MaskParams& P, int64_t* K_user) {
+    if (c->ntiles > 0)
+        hipLaunchKernelGGL(mask_count_kernel, dim3(c->ntiles), dim3(BLOCK), 0, c->stream, P, c->d_tile);
+    hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_tile, c->ntiles, c->msg_ld,
+                       c->d_K, K_user, c->d_flag);
+    SAPS_HIP(c, hipGetLastError());
+    return SAPS_OK;
+}
+
+uint32_t list_grid_x(const saps_ctx* c) {
+    const int64_t b = (c->msg_ld + BLOCK - 1) / BLOCK;
+    return (uint32_t)std::max<int64_t>(1, std::min<int64_t>(b, LIST_GRID_X_MAX));
+}
+
+template <int MODE, int PPB>
+void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, dim3 grid) {
+    if (c->nontemporal)
+        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true>), grid, dim3(BLOCK), 0, c->stream, P, A);
+    else
+        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false>), grid, dim3(BLOCK), 0, c->stream, P, A);
+}
+
+template <int MODE>
+void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A) {
+    int ppb = c->ppb;
+    const uint32_t gx = c->xcd_remap ? 8u * ((c->ntiles + 7u) / 8u) : c->ntiles;
+    A.xcd_remap = c->xcd_remap;
+    const dim3 grid(gx, (uint32_t)((A.n_units + ppb - 1) / ppb));
+    switch (ppb) {
+        case 1: launch_fused_nt<MODE, 1>(c, P, A, grid); break;
+        case 2: launch_fused_nt<MODE, 2>(c, P, A, grid); break;
+        case 4: launch_fused_nt<MODE, 4>(c, P, A, grid); break;
+        case 8: launch_fused_nt<MODE, 8>(c, P, A, grid); break;
+        default: launch_fused_nt<MODE, 16>(c, P, A, grid); break;
+    }
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t saps_abi_version(void) { return 1; }
+
+const char* saps_last_error(const saps_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+
+saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, void* hip_stream) {
+    if (!out) return SAPS_EINVAL;
+    *out = nullptr;
+    if (!L || !L->seg_off || !L->seg_c) return SAPS_EINVAL;
+    if (L->n < 1 || L->n > MAX_WORKERS || L->N < 0 || L->N > MAX_N || L->ld < L->N || (L->ld & 3) || L->n_seg < 1)
+        return SAPS_EINVAL;
+    if (msg_ld < 0 || (msg_ld & 3)) return SAPS_EINVAL;
+    if (L->seg_off[0] != 0 || L->seg_off[L->n_seg] != L->N) return SAPS_EINVAL;
+    std::vector<uint32_t> seg_end;
+    std::vector<uint64_t> seg_T;
+    double expK = 0.0;
+    for (int32_t s = 0; s < L->n_seg; ++s) {
+        const int64_t a = L->seg_off[s], b = L->seg_off[s + 1];
+        const double cs = L->seg_c[s];
+        if (b < a || !(cs >= 1.0)) return SAPS_EINVAL;          // also rejects NaN
+        if (b == a) continue;
+        const uint64_t T = (uint64_t)std::floor(4294967296.0 / cs);
+        expK += (double)(b - a) * ((double)T / 4294967296.0);
+        if (!seg_T.empty() && seg_T.back() == T) seg_end.back() = (uint32_t)b;
+        else { seg_end.push_back((uint32_t)b); seg_T.push_back(T); }
+    }
+    if (seg_T.empty()) { seg_end.push_back((uint32_t)L->N); seg_T.push_back(0); }
+
+    saps_ctx* c = new (std::nothrow) saps_ctx;
+    if (!c) return SAPS_EINVAL;
+    c->n = L->n; c->N = L->N; c->ld = L->ld; c->msg_ld = msg_ld;
+    c->stream = (hipStream_t)hip_stream;
+    c->ntiles = (uint32_t)((L->N + TILE - 1) / TILE);
+    c->n_seg = (int32_t)seg_T.size();
+    c->T0 = seg_T[0];
+    c->density = L->N > 0 ? expK / (double)L->N : 0.0;
+
+    hipError_t e = hipSuccess;
+    auto chk = [&](hipError_t r) { if (e == hipSuccess && r != hipSuccess) e = r; };
+    chk(hipMalloc(&c->d_seg_end, sizeof(uint32_t) * seg_end.size()));
+    chk(hipMalloc(&c->d_seg_T, sizeof(uint64_t) * seg_T.size()));
+    chk(hipMalloc(&c->d_tile, sizeof(uint32_t) * ((size_t)c->ntiles + 1)));
+    chk(hipMalloc(&c->d_K, sizeof(int64_t)));
+    chk(hipMalloc(&c->d_flag, sizeof(int32_t)));
+    chk(hipMalloc(&c->d_idx, sizeof(uint32_t) * (size_t)std::max<int64_t>(msg_ld, 4)));
+    chk(hipMalloc(&c->d_match, sizeof(int32_t) * 3 * (size_t)c->n));
+    for (int r = 0; r < RING; ++r) {
+        chk(hipHostMalloc(&c->ring[r].host, sizeof(int32_t) * 3 * (size_t)c->n, hipHostMallocDefault));
+        chk(hipEventCreateWithFlags(&c->ring[r].done, hipEventDisableTiming));
+    }
+    if (e == hipSuccess) chk(hipMemcpy(c->d_seg_end, seg_end.data(), sizeof(uint32_t) * seg_end.size(), hipMemcpyHostToDevice));
+    if (e == hipSuccess) chk(hipMemcpy(c->d_seg_T, seg_T.data(), sizeof(uint64_t) * seg_T.size(), hipMemcpyHostToDevice));
+    if (e == hipSuccess) chk(hipMemset(c->d_K, 0, sizeof(int64_t)));
+    if (e == hipSuccess) chk(hipMemset(c->d_flag, 0, sizeof(int32_t)));
+    if (e != hipSuccess) {
+        std::fprintf(stderr, "saps_create: %s\n", hipGetErrorString(e));
+        saps_destroy(c);
+        return SAPS_EHIP;
+    }
+    *out = c;
+    return SAPS_OK;
+}
+
+saps_status saps_destroy(saps_ctx* c) {
+    if (!c) return SAPS_EINVAL;
+    (void)hipStreamSynchronize(c->stream);
+    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_tile); (void)hipFree(c->d_K);
+    (void)hipFree(c->d_flag); (void)hipFree(c->d_idx); (void)hipFree(c->d_match);
+    for (int r = 0; r < RING; ++r) {
+        if (c->ring[r].host) (void)hipHostFree(c->ring[r].host);
+        if (c->ring[r].done) (void)hipEventDestroy(c->ring[r].done);
+    }
+    delete c;
+    return SAPS_OK;
+}
+
+saps_status saps_set_tuning(saps_ctx* c, int32_t knob, int32_t value) {
+    if (!c) return SAPS_EINVAL;
+    switch (knob) {
+        case SAPS_TUNE_PAIRS_PER_BLOCK:
+            if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return fail(c, SAPS_EINVAL, "pairs per block");
+            c->ppb = value; return SAPS_OK;
+        case SAPS_TUNE_XCD_REMAP:
+            if (value != 0 && value != 1) return fail(c, SAPS_EINVAL, "xcd remap");
+            c->xcd_remap = value; return SAPS_OK;
+        case SAPS_TUNE_NONTEMPORAL:
+            if (value != 0 && value != 1) return fail(c, SAPS_EINVAL, "nontemporal");
+            c->nontemporal = value; return SAPS_OK;
+        case SAPS_TUNE_EXCHANGE_PATH:
+            if (value < 0 || value > 2) return fail(c, SAPS_EINVAL, "exchange path");
+            c->exchange_path = value; return SAPS_OK;
+        default: return fail(c, SAPS_EINVAL, "unknown knob");
+    }
+}
+
+saps_status saps_sgd_step(saps_ctx* c, float* X, const float* G, float* V, float lr, float mu) {
+    if (!c) return SAPS_EINVAL;
+    if (!X || !G || !aligned16(X) || !aligned16(G) || !aligned16(V)) return fail(c, SAPS_EINVAL, "X/G/V null or misaligned");
+    if (!V && mu != 0.0f) return fail(c, SAPS_EINVAL, "momentum needs V");
+    if (c->N == 0) return SAPS_OK;
+    const uint32_t gx = (uint32_t)(((c->N + 3) / 4 + BLOCK - 1) / BLOCK);
+    const dim3 grid(gx, (uint32_t)c->n);
+    const uint32_t N = (uint32_t)c->N;
+    if (V) {
+        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
+        else hipLaunchKernelGGL((sgd_kernel<true, false>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
+    } else {
+        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<false, true>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
+        else hipLaunchKernelGGL((sgd_kernel<false, false>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
+    }
+    SAPS_HIP(c, hipGetLastError());
+    return SAPS_OK;
+}
+
+saps_status saps_mask_compact(saps_ctx* c, const float* X, uint64_t seed, uint64_t round,
+                              uint32_t* idx, float* msg, int64_t* K_dev) {
+    if (!c) return SAPS_EINVAL;
+    if (!X || !idx || !msg || !K_dev) return fail(c, SAPS_EINVAL, "null pointer");
+    if (!aligned16(X) || !aligned16(idx) || !aligned16(msg) || (reinterpret_cast<uintptr_t>(K_dev) & 7u))
+        return fail(c, SAPS_EINVAL, "misaligned pointer");
+    const MaskParams P = mask_params(c, seed, round);
+    saps_status s = enqueue_count_scan(c, P, K_dev);
+    if (s) return s;
+    if (c->ntiles == 0) return SAPS_OK;
+    hipLaunchKernelGGL(idx_scatter_kernel, dim3(c->ntiles), dim3(BLOCK), 0, c->stream, P, c->d_tile, c->d_K, c->msg_ld, idx);
+    hipLaunchKernelGGL(compact_values_kernel, dim3(list_grid_x(c), (uint32_t)c->n), dim3(BLOCK), 0, c->stream,
+                       X, c->ld, idx, c->d_K, c->msg_ld, msg, c->msg_ld);
+    SAPS_HIP(c, hipGetLastError());
+    return SAPS_OK;
+}
+
+saps_status saps_merge(saps_ctx* c, float* X, const int32_t* peer, const uint32_t* idx, const float* msg,
+                       const int64_t* K_dev) {
+    if (!c) return SAPS_EINVAL;
+    if (!X || !peer || !idx || !msg || !K_dev) return fail(c, SAPS_EINVAL, "null pointer");
+    if (!aligned16(X) || !aligned16(idx) || !aligned16(msg) || (reinterpret_cast<uintptr_t>(K_dev) & 7u))
+        return fail(c, SAPS_EINVAL, "misaligned pointer");
+    if (!matching_ok(c->n, peer)) return fail(c, SAPS_EMATCH, "peer[] is not an involution of [0, n)");
+    int32_t n_units = 0;
+    saps_status s = upload_matching(c, peer, &n_units);
+    if (s) return s;
+    if (c->N == 0) return SAPS_OK;
+    hipLaunchKernelGGL(merge_kernel, dim3(list_grid_x(c), (uint32_t)c->n), dim3(BLOCK), 0, c->stream,
+                       X, c->ld, c->d_match, idx, msg, c->msg_ld, K_dev, c->msg_ld);
+    SAPS_HIP(c, hipGetLastError());
+    return SAPS_OK;
+}
+
+saps_status saps_round(saps_ctx* c, float* X, const float* G, float* V, float lr, float mu,
+                       uint64_t seed, uint64_t round, const int32_t* peer,
+                       uint32_t* idx, float* msg, int64_t* K_dev) {
+    if (!c) return SAPS_EINVAL;
+    if (!X || !peer) return fail(c, SAPS_EINVAL, "null pointer");
+    if (!aligned16(X) || !aligned16(G) || !aligned16(V) || !aligned16(idx) || !aligned16(msg) ||
+        (reinterpret_cast<uintptr_t>(K_dev) & 7u))
+        return fail(c, SAPS_EINVAL, "misaligned pointer");
+    if (G && !V && mu != 0.0f) return fail(c, SAPS_EINVAL, "momentum needs V");
+    if (!matching_ok(c->n, peer)) return fail(c, SAPS_EMATCH, "peer[] is not an involution of [0, n)");
+    int32_t n_units = 0;
+    saps_status s = upload_matching(c, peer, &n_units);
+    if (s) return s;
+    const MaskParams P = mask_params(c, seed, round);
+    s = enqueue_count_scan(c, P, K_dev);
+    if (s) return s;
+    if (c->ntiles == 0) return SAPS_OK;
+
+    FusedArgs A;
+    A.X = X; A.G = G; A.V = V; A.ld = c->ld;
+    A.units = c->d_match + c->n; A.n_units = n_units;
+    A.lr = lr; A.mu = mu;
+    A.tile_base = c->d_tile; A.K_int = c->d_K; A.cap = c->msg_ld;
+    A.idx = idx; A.msg = msg; A.msg_ld = c->msg_ld;
+    A.ntiles = c->ntiles; A.xcd_remap = 0;
+
+    if (G) {
+        if (V) launch_fused<0>(c, P, A); else launch_fused<1>(c, P, A);
+    } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 0.125)) {
+        launch_fused<2>(c, P, A);                     // dense masks: walk the tiles
+    } else {
+        uint32_t* list = idx ? idx : c->d_idx;        // sparse masks: go through the index list
+        hipLaunchKernelGGL(idx_scatter_kernel, dim3(c->ntiles), dim3(BLOCK), 0, c->stream, P, c->d_tile, c->d_K, c->msg_ld, list);
+        hipLaunchKernelGGL(exchange_list_kernel, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
+                           X, c->ld, c->d_match + c->n, list, c->d_K, c->msg_ld, msg, c->msg_ld);
+    }
+    SAPS_HIP(c, hipGetLastError());
+    return SAPS_OK;
+}
+
+saps_status saps_poll_status(saps_ctx* c, int64_t* K_host) {
+    if (!c) return SAPS_EINVAL;
+    SAPS_HIP(c, hipStreamSynchronize(c->stream));
+    int32_t flag = 0;
+    SAPS_HIP(c, hipMemcpy(&flag, c->d_flag, sizeof(flag), hipMemcpyDeviceToHost));
+    if (K_host) SAPS_HIP(c, hipMemcpy(K_host, c->d_K, sizeof(int64_t), hipMemcpyDeviceToHost));
+    if (flag) {
+        SAPS_HIP(c, hipMemset(c->d_flag, 0, sizeof(int32_t)));
+        return fail(c, SAPS_ECAPACITY, "K exceeded the message capacity; the round was skipped");
+    }
+    return SAPS_OK;
+}
+
+saps_status saps_stream_copy(saps_ctx* c, float* dst, const float* src, int64_t count) {
+    if (!c) return SAPS_EINVAL;
+    if (!dst || !src || count < 0 || (count & 3) || !aligned16(dst) || !aligned16(src)) return fail(c, SAPS_EINVAL, "copy arguments");
+    if (count == 0) return SAPS_OK;
+    const int64_t c4 = count / 4;
+    const int64_t blocks = (c4 + BLOCK - 1) / BLOCK;
+    if (blocks > 0x7FFFFFFFll) return fail(c, SAPS_EINVAL, "copy too large");
+    if (c->nontemporal) hipLaunchKernelGGL(stream_copy_kernel<true>, dim3((uint32_t)blocks), dim3(BLOCK), 0, c->stream, dst, src, c4);
+    else hipLaunchKernelGGL(stream_copy_kernel<false>, dim3((uint32_t)blocks), dim3(BLOCK), 0, c->stream, dst, src, c4);
+    SAPS_HIP(c, hipGetLastError());
+    return SAPS_OK;
+}
+
+}  // extern "C"

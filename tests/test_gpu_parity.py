@@ -1,0 +1,373 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element.
+
+Bars: K, idx, msg and averaged values bit-exact; the momentum update bit-exact under the
+two-FMA reading and in any case within 1e-6 relative.
+"""
+import numpy as np
+import pytest
+
+from oracle import saps_oracle as O
+from paper_2002_09692_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_2002_09692_amd import binding
+    binding.load_library()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(a).cuda()
+
+
+def bits(a):
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
+def assert_bits(got, want, what):
+    g, w = bits(got), bits(want)
+    if not np.array_equal(g, w):
+        bad = np.argwhere(g != w)
+        raise AssertionError(f"{what}: {len(bad)} of {g.size} words differ, first at {bad[0]}: "
+                             f"{got[tuple(bad[0])]!r} vs {want[tuple(bad[0])]!r}")
+
+
+def rand_models(n, N, ld, seed, pad=777.0, scale=0.05):
+    rng = np.random.default_rng(seed)
+    X = np.full((n, ld), pad, np.float32)
+    X[:, :N] = scale * rng.standard_normal((n, N), dtype=np.float32)
+    return X
+
+
+def rand_peer(n, seed, singles=0):
+    rng = np.random.default_rng(seed)
+    peer = synth.random_perfect_matching(n, rng)
+    for i in rng.permutation(n)[:singles]:
+        p = peer[i]
+        peer[i], peer[p] = i, p
+    return peer
+
+
+def run_round_both(B, n, N, ld, seg_c, seg_off, seed, rnd, peer, fused, mu=0.9, lr=0.1, msg_ld=None, tuning=(),
+                   with_v=True, outputs=True):
+    X0 = rand_models(n, N, ld, 1)
+    G0 = rand_models(n, N, ld, 2, pad=555.0, scale=1e-3) if fused else None
+    V0 = rand_models(n, N, ld, 3, pad=333.0, scale=1e-3) if (fused and with_v) else None
+    if msg_ld is None:
+        msg_ld = (N + 3) // 4 * 4
+    # oracle
+    Xo = X0[:, :].copy(); Vo = None if V0 is None else V0.copy()
+    rc_o, K_o, idx_o, msg_o = O.round_(Xo, G0, Vo, N, lr, mu if with_v else 0.0, seed, rnd, peer, seg_c, seg_off, msg_ld=msg_ld)
+    # device
+    X = dev(X0); G = None if G0 is None else dev(G0); V = None if V0 is None else dev(V0)
+    idx = torch.full((max(msg_ld, 4),), -1, dtype=torch.int32, device="cuda") if outputs else None
+    msg = torch.full((n, msg_ld), -5.0, dtype=torch.float32, device="cuda") if outputs else None
+    Kd = torch.full((1,), -1, dtype=torch.int64, device="cuda") if outputs else None
+    with B.SapsContext(n, N, ld, msg_ld, seg_c, seg_off) as ctx:
+        for k, v in tuning:
+            ctx.saps_set_tuning(k, v)
+        ctx.saps_round(X, G, V, lr, mu if with_v else 0.0, seed, rnd, peer, idx, msg, Kd)
+        st, K = ctx.saps_poll_status()
+    return dict(rc_o=rc_o, K_o=K_o, idx_o=idx_o, msg_o=msg_o, Xo=Xo, Vo=Vo, st=st, K=K, X=X.cpu().numpy(),
+                V=None if V is None else V.cpu().numpy(), idx=None if idx is None else idx.cpu().numpy().view(np.uint32),
+                msg=None if msg is None else msg.cpu().numpy(), Kd=None if Kd is None else int(Kd.item()),
+                X0=X0, V0=V0, msg_ld=msg_ld)
+
+
+def check_round(r, N):
+    assert r["rc_o"] == O.OK and r["st"] == 0
+    K = r["K_o"]
+    assert r["K"] == K
+    if r["Kd"] is not None:
+        assert r["Kd"] == K
+        assert np.array_equal(r["idx"][:K], r["idx_o"][:K]), "idx"
+        assert np.all(r["idx"][K:] == 0xFFFFFFFF), "idx written beyond K"
+        assert_bits(r["msg"][:, :K], r["msg_o"][:, :K], "msg")
+        assert np.all(r["msg"][:, K:] == -5.0), "msg written beyond K"
+    assert_bits(r["X"], r["Xo"], "X")            # includes the padding columns: never touched
+    if r["V"] is not None:
+        assert_bits(r["V"], r["Vo"], "V")
+        np.testing.assert_allclose(r["V"][:, :N], r["Vo"][:, :N], rtol=1e-6, atol=0)
+    np.testing.assert_allclose(r["X"][:, :N], r["Xo"][:, :N], rtol=1e-6, atol=0)
+
+
+# ------------------------------------------------------------------------------ stages
+@pytest.mark.parametrize("N,ld", [(5000, 5056), (4096, 4096), (1023, 1024), (3, 4), (1, 4), (10_001, 10_004)])
+@pytest.mark.parametrize("with_v", [True, False])
+def test_sgd_step(B, N, ld, with_v):
+    n = 3
+    X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2, pad=9.0); V0 = rand_models(n, N, ld, 3, pad=8.0)
+    Xo, Vo = X0.copy(), V0.copy()
+    mu = 0.9 if with_v else 0.0
+    assert O.sgd_step(Xo, G0, Vo if with_v else None, 0.1, mu, N=N) == O.OK
+    X, G, V = dev(X0), dev(G0), dev(V0)
+    with B.SapsContext(n, N, ld, 0) as ctx:
+        ctx.saps_sgd_step(X, G, V if with_v else None, 0.1, mu)
+        assert ctx.saps_poll_status()[0] == 0
+    assert_bits(X.cpu().numpy(), Xo, "X")
+    assert_bits(V.cpu().numpy(), Vo, "V")
+    assert_bits(G.cpu().numpy(), G0, "G")
+
+
+@pytest.mark.parametrize("N,c", [(100_000, 100.0), (5000, 4.0), (1030, 1.0), (2, 2.0), (50_001, 1000.0), (7777, 2.0**33)])
+def test_mask_compact_then_merge(B, N, c):
+    n = 5
+    ld = (N + 63) // 64 * 64
+    msg_ld = (N + 3) // 4 * 4
+    X0 = rand_models(n, N, ld, 7)
+    peer = rand_peer(n, 3)                                   # odd n: one worker unmatched
+    rc, K, idx_o, msg_o = O.mask_compact(X0, N, 11, 4, c, msg_ld=msg_ld)
+    assert rc == O.OK
+    Xo = X0.copy()
+    assert O.merge(Xo, N, peer, idx_o, msg_o, K) == O.OK
+    X = dev(X0)
+    idx = torch.full((max(msg_ld, 4),), -1, dtype=torch.int32, device="cuda")
+    msg = torch.full((n, msg_ld), -5.0, device="cuda")
+    Kd = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    with B.SapsContext(n, N, ld, msg_ld, c) as ctx:
+        ctx.saps_mask_compact(X, 11, 4, idx, msg, Kd)
+        assert ctx.saps_poll_status() == (0, K)
+        assert_bits(X.cpu().numpy(), X0, "X after compaction (read only)")
+        ctx.saps_merge(X, peer, idx, msg, Kd)
+        assert ctx.saps_poll_status()[0] == 0
+    assert int(Kd.item()) == K
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K])
+    assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], "msg")
+    assert np.all(msg.cpu().numpy()[:, K:] == -5.0)
+    assert_bits(X.cpu().numpy(), Xo, "X after merge")
+
+
+# ------------------------------------------------------------------------- whole round
+SHAPES = [
+    # n, N, ld, c
+    (4, 100_000, 100_032, 100.0),      # several hundred tiles... ~98 tiles, N % 1024 != 0
+    (6, 10_242, 10_304, 4.0),          # N % 4 == 2: ragged Philox block
+    (5, 4097, 4100, 2.0),              # odd n, one coordinate into the 5th tile
+    (2, 1024, 1024, 1.0),              # exactly one tile, everything exchanged
+    (3, 5, 8, 1.0),                    # smaller than a tile and than a wave
+    (2, 3, 4, 2.0),                    # smaller than one Philox block
+    (8, 65_537, 65_600, 1000.0),       # very sparse
+]
+
+
+@pytest.mark.parametrize("n,N,ld,c", SHAPES)
+@pytest.mark.parametrize("ppb", [1, 4, 16])
+def test_fused_round_with_update(B, n, N, ld, c, ppb):
+    peer = rand_peer(n, n + N, singles=1 if n > 2 else 0)
+    r = run_round_both(B, n, N, ld, c, None, 5, 3, peer, fused=True, tuning=[(B.TUNE_PAIRS_PER_BLOCK, ppb)])
+    check_round(r, N)
+
+
+@pytest.mark.parametrize("knobs", [[(1, 1)], [(2, 1)], [(1, 1), (2, 1), (0, 2)]])
+def test_fused_round_launch_knobs_do_not_change_results(B, knobs):
+    n, N, ld = 6, 70_003, 70_016
+    r = run_round_both(B, n, N, ld, 10.0, None, 8, 2, rand_peer(n, 1), fused=True, tuning=knobs)
+    check_round(r, N)
+
+
+def test_fused_round_without_momentum_buffer(B):
+    n, N, ld = 4, 33_333, 33_344
+    r = run_round_both(B, n, N, ld, 8.0, None, 1, 1, rand_peer(n, 2), fused=True, with_v=False)
+    check_round(r, N)
+
+
+def test_fused_round_without_optional_outputs(B):
+    n, N, ld = 4, 20_000, 20_032
+    r = run_round_both(B, n, N, ld, 16.0, None, 1, 9, rand_peer(n, 2), fused=True, outputs=False)
+    check_round(r, N)
+
+
+@pytest.mark.parametrize("n,N,ld,c", SHAPES)
+@pytest.mark.parametrize("path", [1, 2])
+def test_exchange_only_round_both_paths(B, n, N, ld, c, path):
+    peer = rand_peer(n, n * 3 + N, singles=1 if n > 2 else 0)
+    r = run_round_both(B, n, N, ld, c, None, 2**40 + 17, 2**35 + 1, peer, fused=False, tuning=[(B.TUNE_EXCHANGE_PATH, path)])
+    check_round(r, N)
+
+
+@pytest.mark.parametrize("path", [1, 2])
+def test_exchange_only_without_optional_outputs(B, path):
+    n, N, ld = 4, 30_000, 30_016
+    r = run_round_both(B, n, N, ld, 50.0, None, 3, 3, rand_peer(n, 5), fused=False, outputs=False,
+                       tuning=[(B.TUNE_EXCHANGE_PATH, path)])
+    check_round(r, N)
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_per_segment_ratios_at_unaligned_offsets(B, fused):
+    n, N, ld = 4, 30_011, 30_016
+    off = [0, 3, 10, 10, 4099, 20_001, N]
+    cs = [1.0, 2.0, 7.0, 100.0, 10.0, 1000.0]
+    r = run_round_both(B, n, N, ld, cs, off, 9, 2, rand_peer(n, 4), fused=fused)
+    check_round(r, N)
+    for path in (1, 2):
+        r = run_round_both(B, n, N, ld, cs, off, 9, 2, rand_peer(n, 4), fused=False, tuning=[(B.TUNE_EXCHANGE_PATH, path)])
+        check_round(r, N)
+
+
+def test_many_tiny_segments(B):
+    # segments shorter than a tile, a wave and a Philox block (BN-sized tensors)
+    rng = np.random.default_rng(0)
+    sizes = rng.integers(1, 70, size=400).tolist() + [5000] + rng.integers(1, 9, size=300).tolist()
+    off = synth.segment_offsets(sizes)
+    N = int(off[-1]); ld = (N + 63) // 64 * 64
+    cs = rng.choice([1.0, 3.0, 10.0, 100.0], size=len(sizes)).tolist()
+    for fused in (True, False):
+        r = run_round_both(B, 4, N, ld, cs, off, 4, 4, rand_peer(4, 9), fused=fused)
+        check_round(r, N)
+
+
+def test_identity_matching_and_all_singles(B):
+    n, N, ld = 4, 9000, 9024
+    r = run_round_both(B, n, N, ld, 4.0, None, 1, 1, np.arange(n, dtype=np.int32), fused=True)
+    check_round(r, N)
+    r = run_round_both(B, n, N, ld, 4.0, None, 1, 1, np.arange(n, dtype=np.int32), fused=False)
+    check_round(r, N)
+    assert_bits(r["X"], r["X0"], "identity matching without update changes nothing")
+
+
+def test_fused_equals_unfused_sequence_on_device(B):
+    n, N, ld, c = 6, 50_003, 50_048, 20.0
+    msg_ld = 50_004
+    X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2, scale=1e-3); V0 = rand_models(n, N, ld, 3, scale=1e-3)
+    peer = rand_peer(n, 6)
+    outs = []
+    for fused in (True, False):
+        X, G, V = dev(X0), dev(G0), dev(V0)
+        idx = torch.zeros(msg_ld, dtype=torch.int32, device="cuda"); msg = torch.zeros((n, msg_ld), device="cuda")
+        Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+        with B.SapsContext(n, N, ld, msg_ld, c) as ctx:
+            if fused:
+                ctx.saps_round(X, G, V, 0.1, 0.9, 4, 2, peer, idx, msg, Kd)
+            else:
+                ctx.saps_sgd_step(X, G, V, 0.1, 0.9)
+                ctx.saps_mask_compact(X, 4, 2, idx, msg, Kd)
+                ctx.saps_merge(X, peer, idx, msg, Kd)
+            assert ctx.saps_poll_status()[0] == 0
+        outs.append([t.cpu().numpy() for t in (X, V, idx, msg, Kd)])
+    for a, b, name in zip(outs[0], outs[1], ["X", "V", "idx", "msg", "K"]):
+        assert np.array_equal(a.view(np.uint32) if a.dtype == np.float32 else a, b.view(np.uint32) if b.dtype == np.float32 else b), name
+
+
+def test_multi_round_trajectory_cfg1(B):
+    # configuration 1: n=4, N=100000, c=100, 10 fused rounds, fresh gradients and a fresh matching per round
+    wl = synth.workload("cfg1")
+    ld = wl.ld(); cap = synth.recommended_capacity(wl)
+    X0 = synth.make_models(wl, ld)
+    Xo = X0.copy(); Vo = np.zeros_like(Xo)
+    X = dev(X0); V = torch.zeros_like(X)
+    idx = torch.zeros(cap, dtype=torch.int32, device="cuda"); msg = torch.zeros((wl.n, cap), device="cuda")
+    Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+    with B.SapsContext(wl.n, wl.N, ld, cap, 100.0) as ctx:
+        for t in range(1, wl.rounds + 1):
+            G0 = synth.make_grads(wl, t, ld); peer = wl.peers(t)
+            rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, wl.N, wl.lr, wl.mu, 0, t, peer, 100.0, msg_ld=cap)
+            assert rc == O.OK
+            ctx.saps_round(X, dev(G0), V, wl.lr, wl.mu, 0, t, peer, idx, msg, Kd)
+            assert ctx.saps_poll_status() == (0, K)
+            assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K])
+            assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], f"msg round {t}")
+            assert_bits(X.cpu().numpy(), Xo, f"X round {t}")
+            assert_bits(V.cpu().numpy(), Vo, f"V round {t}")
+
+
+def test_c1_fixed_matching_pairs_become_identical(B):
+    n, N, ld = 4, 5000, 5056
+    X = dev(rand_models(n, N, ld, 1)); V = torch.zeros_like(X)
+    peer = np.array([2, 3, 0, 1], np.int32)
+    with B.SapsContext(n, N, ld, 5000, 1.0) as ctx:
+        for t in range(1, 4):
+            G = dev(rand_models(n, N, ld, 10 + t, scale=1e-3))
+            ctx.saps_round(X, G, V, 0.1, 0.9, 1, t, peer)
+            assert ctx.saps_poll_status() == (0, N)
+            h = X.cpu().numpy()[:, :N]
+            assert_bits(h[0], h[2], "pair (0,2)"); assert_bits(h[1], h[3], "pair (1,3)")
+            assert not np.array_equal(h[0], h[1])
+
+
+# --------------------------------------------------------------------- errors and edges
+def test_capacity_overflow_skips_the_round(B):
+    n, N, ld = 4, 40_000, 40_000
+    X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2); V0 = rand_models(n, N, ld, 3)
+    peer = rand_peer(n, 1)
+    for fused in (True, False):
+        for path in (1, 2):
+            X, G, V = dev(X0), dev(G0), dev(V0)
+            idx = torch.full((100,), -1, dtype=torch.int32, device="cuda"); msg = torch.full((n, 100), -5.0, device="cuda")
+            Kd = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+            with B.SapsContext(n, N, ld, 100, 2.0) as ctx:
+                ctx.saps_set_tuning(B.TUNE_EXCHANGE_PATH, path)
+                ctx.saps_round(X, G if fused else None, V if fused else None, 0.1, 0.9, 0, 1, peer, idx, msg, Kd)
+                st, K = ctx.saps_poll_status()
+                assert st == B.ECAPACITY and K == int(O.mask(N, 0, 1, 2.0).sum()) and int(Kd.item()) == K
+                assert ctx.saps_poll_status()[0] == 0                      # flag is cleared by the poll
+                # un-fused entries honour the same rule
+                ctx.saps_mask_compact(X, 0, 1, idx, msg, Kd)
+                ctx.saps_merge(X, peer, idx, msg, Kd)
+                assert ctx.saps_poll_status()[0] == B.ECAPACITY
+            assert_bits(X.cpu().numpy(), X0, "X"); assert_bits(V.cpu().numpy(), V0, "V")
+            assert np.all(idx.cpu().numpy() == -1) and np.all(msg.cpu().numpy() == -5.0)
+
+
+def test_host_side_argument_errors(B):
+    n, N, ld = 4, 1000, 1000
+    X = dev(rand_models(n, N, ld, 1))
+    with pytest.raises(B.SapsError) as e:
+        B.SapsContext(n, N, 999, 1000)
+    assert e.value.status == B.EINVAL
+    with pytest.raises(B.SapsError):
+        B.SapsContext(n, N, 1002, 1000)                        # ld % 4
+    with pytest.raises(B.SapsError):
+        B.SapsContext(n, N, ld, 1000, 0.5)                     # c < 1
+    with pytest.raises(B.SapsError):
+        B.SapsContext(n, N, ld, 1000, [2.0, 2.0], [0, 600, 999])   # segments do not end at N
+    with pytest.raises(B.SapsError):
+        B.SapsContext(n, N, ld, 1001)                          # capacity % 4
+    with B.SapsContext(n, N, ld, 1000, 2.0) as ctx:
+        for bad in ([1, 2, 0, 3], [0, 1, 2, 4], [-1, 1, 2, 3], [1, 1, 2, 3]):
+            assert ctx.saps_round(X, None, None, 0, 0, 0, 1, np.array(bad), check=False) == B.EMATCH
+            assert ctx.saps_merge(X, np.array(bad), torch.zeros(1000, dtype=torch.int32, device="cuda"),
+                                  torch.zeros((n, 1000), device="cuda"), torch.zeros(1, dtype=torch.int64, device="cuda"),
+                                  check=False) == B.EMATCH
+        G = dev(rand_models(n, N, ld, 2))
+        assert ctx.saps_round(X, G, None, 0.1, 0.9, 0, 1, np.array([1, 0, 3, 2]), check=False) == B.EINVAL
+        assert ctx.saps_sgd_step(X, G, None, 0.1, 0.9, check=False) == B.EINVAL
+        assert ctx.saps_set_tuning(0, 3, check=False) == B.EINVAL
+        assert ctx.saps_set_tuning(99, 0, check=False) == B.EINVAL
+        assert ctx.saps_poll_status()[0] == 0
+
+
+def test_empty_model(B):
+    n = 2
+    X = torch.ones((n, 4), device="cuda")                     # N = 0 with a padded row stride of 4
+    Kd = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+    with B.SapsContext(n, 0, 4, 0, 4.0) as ctx:
+        ctx.saps_round(X, None, None, 0, 0, 1, 1, np.array([1, 0]), None, None, Kd)
+        assert ctx.saps_poll_status() == (0, 0)
+    assert int(Kd.item()) == 0 and bool((X == 1).all())
+
+
+def test_special_values_travel_through_merge(B):
+    n, N, ld = 2, 8, 8
+    inf, nan, tiny = np.float32(np.inf), np.float32(np.nan), np.float32(1e-45)
+    a = np.array([inf, inf, nan, -0.0, tiny, 3 * tiny, 3.4e38, 1.0], np.float32)
+    b = np.array([1.0, -inf, 1.0, 0.0, tiny, tiny, 3.4e38, -1.0], np.float32)
+    X0 = np.stack([a, b]); Xo = X0.copy()
+    O.round_(Xo, None, None, N, 0, 0, 0, 1, np.array([1, 0]), 1.0)
+    for path in (1, 2):
+        X = dev(X0)
+        with B.SapsContext(n, N, ld, 8, 1.0) as ctx:
+            ctx.saps_set_tuning(B.TUNE_EXCHANGE_PATH, path)
+            ctx.saps_round(X, None, None, 0, 0, 0, 1, np.array([1, 0]))
+            assert ctx.saps_poll_status() == (0, 8)
+        h = X.cpu().numpy()
+        assert np.array_equal(np.isnan(h), np.isnan(Xo))           # NaN payloads may differ between machines
+        ok = ~np.isnan(Xo)
+        assert np.array_equal(bits(h)[ok], bits(Xo)[ok])           # subnormals, signed zero, overflow to inf
