@@ -115,6 +115,15 @@ enum {
 };
 saps_status saps_set_tuning(saps_ctx* ctx, int32_t knob, int32_t value);
 
+/* Per-kernel timing for benchmarks.  saps_profile_enable(ctx, 1) makes every following
+ * saps_round / saps_sgd_step / saps_stream_copy bracket its dominant kernel (the fused
+ * round kernel, the list exchange kernel, the update kernel, the copy kernel) with a pair of
+ * HIP events on the context's stream (at most 4096 pairs are kept; later launches are not
+ * recorded).  saps_profile_read waits for the stream, returns the number of recorded
+ * launches and the sum of their durations in milliseconds, and forgets them. */
+saps_status saps_profile_enable(saps_ctx* ctx, int32_t on);
+saps_status saps_profile_read(saps_ctx* ctx, int32_t* launches, double* total_ms);
+
 /* Plain device-to-device streaming copy of `count` floats (16-byte aligned, count % 4 == 0)
  * with the same access shape as the round kernels: the bandwidth yardstick of the
  * benchmark and the scale reference for profiler byte counters.  Not part of the method. */

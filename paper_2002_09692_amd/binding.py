@@ -20,7 +20,8 @@ TUNE_PAIRS_PER_BLOCK, TUNE_XCD_REMAP, TUNE_NONTEMPORAL, TUNE_EXCHANGE_PATH = 0, 
 _NAMES = {OK: "SAPS_OK", EINVAL: "SAPS_EINVAL", EMATCH: "SAPS_EMATCH", ECAPACITY: "SAPS_ECAPACITY", EHIP: "SAPS_EHIP"}
 
 EXPORTS = ("saps_abi_version", "saps_create", "saps_destroy", "saps_sgd_step", "saps_mask_compact", "saps_merge",
-           "saps_round", "saps_poll_status", "saps_last_error", "saps_set_tuning", "saps_stream_copy")
+           "saps_round", "saps_poll_status", "saps_last_error", "saps_set_tuning", "saps_stream_copy",
+           "saps_profile_enable", "saps_profile_read")
 
 
 class SapsError(RuntimeError):
@@ -58,6 +59,8 @@ def load_library() -> C.CDLL:
     L.saps_last_error.argtypes = [vp]; L.saps_last_error.restype = C.c_char_p
     L.saps_set_tuning.argtypes = [vp, i32, i32]; L.saps_set_tuning.restype = C.c_int
     L.saps_stream_copy.argtypes = [vp, vp, vp, i64]; L.saps_stream_copy.restype = C.c_int
+    L.saps_profile_enable.argtypes = [vp, i32]; L.saps_profile_enable.restype = C.c_int
+    L.saps_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]; L.saps_profile_read.restype = C.c_int
     _lib = L
     return L
 
@@ -172,3 +175,12 @@ class SapsContext:
     def saps_stream_copy(self, dst: torch.Tensor, src: torch.Tensor, check: bool = True) -> int:
         return self._rc(self._L.saps_stream_copy(self._h, _dev(dst, torch.float32, "dst"), _dev(src, torch.float32, "src"),
                                                  src.numel()), check)
+
+    def saps_profile_enable(self, on: bool) -> int:
+        return self._rc(self._L.saps_profile_enable(self._h, int(on)), True)
+
+    def saps_profile_read(self):
+        """Returns (launches, total_ms) of the dominant kernels recorded since the last read."""
+        cnt = C.c_int32(0); ms = C.c_double(0.0)
+        self._rc(self._L.saps_profile_read(self._h, C.byref(cnt), C.byref(ms)), True)
+        return int(cnt.value), float(ms.value)

@@ -49,6 +49,10 @@ struct saps_ctx {
     uint64_t calls = 0;
     // launch-shape knobs
     int32_t ppb = 4, xcd_remap = 0, nontemporal = 0, exchange_path = 0;
+    // optional event pairs around the dominant kernel of a call
+    bool profiling = false;
+    std::vector<hipEvent_t> ev_pool;    // 2 events per record, created on demand
+    size_t ev_used = 0;
     std::string err;
 };
 
@@ -113,6 +117,26 @@ saps_status upload_matching(saps_ctx* c, const int32_t* peer, int32_t* n_units) 
     SAPS_HIP(c, hipEventRecord(s.done, c->stream));
     s.used = true;
     return SAPS_OK;
+}
+
+constexpr size_t MAX_PROFILE_RECORDS = 4096;
+
+// Records an event on the stream if profiling is on; `second` closes the pair opened before.
+void profile_mark(saps_ctx* c, bool second) {
+    if (!c->profiling) return;
+    if (!second) {
+        if (c->ev_used / 2 >= MAX_PROFILE_RECORDS) return;
+        if (c->ev_pool.size() < c->ev_used + 2) {
+            hipEvent_t a = nullptr, b = nullptr;
+            if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+            c->ev_pool.push_back(a); c->ev_pool.push_back(b);
+        }
+        (void)hipEventRecord(c->ev_pool[c->ev_used], c->stream);
+        c->ev_used += 1;
+    } else if (c->ev_used & 1) {
+        (void)hipEventRecord(c->ev_pool[c->ev_used], c->stream);
+        c->ev_used += 1;
+    }
 }
 
 // K1 + K2: per-tile counts, exclusive tile bases, K and the capacity flag.
@@ -224,6 +248,7 @@ saps_status saps_destroy(saps_ctx* c) {
     (void)hipStreamSynchronize(c->stream);
     (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_tile); (void)hipFree(c->d_K);
     (void)hipFree(c->d_flag); (void)hipFree(c->d_idx); (void)hipFree(c->d_match);
+    for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (int r = 0; r < RING; ++r) {
         if (c->ring[r].host) (void)hipHostFree(c->ring[r].host);
         if (c->ring[r].done) (void)hipEventDestroy(c->ring[r].done);
@@ -259,6 +284,7 @@ saps_status saps_sgd_step(saps_ctx* c, float* X, const float* G, float* V, float
     const uint32_t gx = (uint32_t)(((c->N + 3) / 4 + BLOCK - 1) / BLOCK);
     const dim3 grid(gx, (uint32_t)c->n);
     const uint32_t N = (uint32_t)c->N;
+    profile_mark(c, false);
     if (V) {
         if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
         else hipLaunchKernelGGL((sgd_kernel<true, false>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
@@ -266,6 +292,7 @@ saps_status saps_sgd_step(saps_ctx* c, float* X, const float* G, float* V, float
         if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<false, true>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
         else hipLaunchKernelGGL((sgd_kernel<false, false>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
     }
+    profile_mark(c, true);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;
 }
@@ -331,14 +358,20 @@ saps_status saps_round(saps_ctx* c, float* X, const float* G, float* V, float lr
     A.ntiles = c->ntiles; A.xcd_remap = 0;
 
     if (G) {
+        profile_mark(c, false);
         if (V) launch_fused<0>(c, P, A); else launch_fused<1>(c, P, A);
+        profile_mark(c, true);
     } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 0.125)) {
+        profile_mark(c, false);
         launch_fused<2>(c, P, A);                     // dense masks: walk the tiles
+        profile_mark(c, true);
     } else {
         uint32_t* list = idx ? idx : c->d_idx;        // sparse masks: go through the index list
         hipLaunchKernelGGL(idx_scatter_kernel, dim3(c->ntiles), dim3(BLOCK), 0, c->stream, P, c->d_tile, c->d_K, c->msg_ld, list);
+        profile_mark(c, false);
         hipLaunchKernelGGL(exchange_list_kernel, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
                            X, c->ld, c->d_match + c->n, list, c->d_K, c->msg_ld, msg, c->msg_ld);
+        profile_mark(c, true);
     }
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;
@@ -357,6 +390,27 @@ saps_status saps_poll_status(saps_ctx* c, int64_t* K_host) {
     return SAPS_OK;
 }
 
+saps_status saps_profile_enable(saps_ctx* c, int32_t on) {
+    if (!c) return SAPS_EINVAL;
+    c->profiling = on != 0;
+    return SAPS_OK;
+}
+
+saps_status saps_profile_read(saps_ctx* c, int32_t* launches, double* total_ms) {
+    if (!c || !launches || !total_ms) return SAPS_EINVAL;
+    SAPS_HIP(c, hipStreamSynchronize(c->stream));
+    double sum = 0.0;
+    int32_t cnt = 0;
+    for (size_t k = 0; k + 1 < c->ev_used; k += 2) {
+        float ms = 0.f;
+        SAPS_HIP(c, hipEventElapsedTime(&ms, c->ev_pool[k], c->ev_pool[k + 1]));
+        sum += ms; ++cnt;
+    }
+    c->ev_used = 0;
+    *launches = cnt; *total_ms = sum;
+    return SAPS_OK;
+}
+
 saps_status saps_stream_copy(saps_ctx* c, float* dst, const float* src, int64_t count) {
     if (!c) return SAPS_EINVAL;
     if (!dst || !src || count < 0 || (count & 3) || !aligned16(dst) || !aligned16(src)) return fail(c, SAPS_EINVAL, "copy arguments");
@@ -364,8 +418,10 @@ saps_status saps_stream_copy(saps_ctx* c, float* dst, const float* src, int64_t 
     const int64_t c4 = count / 4;
     const int64_t blocks = (c4 + BLOCK - 1) / BLOCK;
     if (blocks > 0x7FFFFFFFll) return fail(c, SAPS_EINVAL, "copy too large");
+    profile_mark(c, false);
     if (c->nontemporal) hipLaunchKernelGGL(stream_copy_kernel<true>, dim3((uint32_t)blocks), dim3(BLOCK), 0, c->stream, dst, src, c4);
     else hipLaunchKernelGGL(stream_copy_kernel<false>, dim3((uint32_t)blocks), dim3(BLOCK), 0, c->stream, dst, src, c4);
+    profile_mark(c, true);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;
 }
