@@ -67,7 +67,7 @@ typedef struct {
 
 /* Creates a context for one layout.  msg_ld = capacity of a packed message row (floats,
  * multiple of 4, >= 0).  hip_stream = hipStream_t to enqueue on (NULL = default stream).
- * Allocates the private scratch (about 4 bytes per 1024 coordinates + 4*msg_ld + 16*n). */
+ * Allocates the private scratch (about 4 bytes per 256 coordinates + 4*msg_ld + 16*n). */
 saps_status saps_create(saps_ctx** out, const saps_layout* layout, int64_t msg_ld, void* hip_stream);
 saps_status saps_destroy(saps_ctx* ctx);
 
@@ -108,7 +108,7 @@ const char* saps_last_error(const saps_ctx* ctx);
 /* Launch-shape knobs for measurement sweeps; results never depend on them.
  * Unknown knob or out-of-range value: SAPS_EINVAL. */
 enum {
-    SAPS_TUNE_PAIRS_PER_BLOCK = 0, /* fused round: matched pairs handled per workgroup: 1, 2, 4, 8, 16 */
+    SAPS_TUNE_PAIRS_PER_BLOCK = 0, /* fused round: matched pairs handled per workgroup: 1, 2, 4, 8 */
     SAPS_TUNE_XCD_REMAP = 1,       /* fused round: 0 = tiles in launch order, 1 = contiguous tile range per XCD */
     SAPS_TUNE_NONTEMPORAL = 2,     /* fused round and local step: 0 = plain, 1 = non-temporal loads/stores */
     SAPS_TUNE_EXCHANGE_PATH = 3    /* exchange-only round: 0 = by expected density, 1 = index list, 2 = tile walk */

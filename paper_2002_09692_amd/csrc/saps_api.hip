@@ -21,7 +21,7 @@ constexpr int32_t MAX_WORKERS = 65535;
 constexpr uint32_t LIST_GRID_X_MAX = 1024;
 
 struct Slot {
-    int32_t* host = nullptr;            // pinned: peer[n] followed by units[2n]
+    int32_t* host = nullptr;            // pinned: units[2n]
     hipEvent_t done = nullptr;
     bool used = false;
 };
@@ -40,15 +40,17 @@ struct saps_ctx {
     uint32_t* d_seg_end = nullptr;
     uint64_t* d_seg_T = nullptr;
     // scratch
-    uint32_t* d_tile = nullptr;         // ntiles + 1 counts / exclusive bases
+    uint32_t ngroups = 0;
+    uint32_t* d_tile = nullptr;         // ntiles kept counts, one per wave tile
+    uint32_t* d_grp = nullptr;          // ngroups counts, then exclusive bases after the scan
     int64_t* d_K = nullptr;             // K of the most recent mask generation
     int32_t* d_flag = nullptr;          // sticky capacity flag
     uint32_t* d_idx = nullptr;          // msg_ld entries, used when the caller passes idx == NULL
-    int32_t* d_match = nullptr;         // peer[n] followed by units[2n]
+    int32_t* d_match = nullptr;         // units[2n], only used when the list is too long for the kernel arguments
     Slot ring[RING];
     uint64_t calls = 0;
     // launch-shape knobs
-    int32_t ppb = 4, xcd_remap = 0, nontemporal = 0, exchange_path = 0;
+    int32_t ppb = 1, xcd_remap = 0, nontemporal = 1, exchange_path = 0;
     // optional event pairs around the dominant kernel of a call
     bool profiling = false;
     std::vector<hipEvent_t> ev_pool;    // 2 events per record, created on demand
@@ -100,24 +102,36 @@ bool matching_ok(int32_t n, const int32_t* peer) {
     return true;
 }
 
-// Stages peer[] and the unit list (pairs i < p, singles i == p) through a pinned slot and
-// enqueues the upload.  Returns the number of units.
-saps_status upload_matching(saps_ctx* c, const int32_t* peer, int32_t* n_units) {
+// Builds the unit list of a matching (pairs i < p, singles i == p).  Up to MAX_INLINE_UNITS
+// units ride in the kernel arguments; longer lists are staged through a pinned slot and
+// uploaded on the stream.
+saps_status make_units(saps_ctx* c, const int32_t* peer, Units* U, int32_t* n_units) {
+    int32_t u = 0;
+    for (int32_t i = 0; i < c->n; ++i) u += (peer[i] >= i);
+    *n_units = u;
+    if (u <= MAX_INLINE_UNITS) {
+        U->dev = nullptr;
+        int32_t k = 0;
+        for (int32_t i = 0; i < c->n; ++i)
+            if (peer[i] >= i) U->packed[k++] = (uint32_t)i | ((uint32_t)peer[i] << 16);
+        for (; k < MAX_INLINE_UNITS; ++k) U->packed[k] = 0u;
+        return SAPS_OK;
+    }
     Slot& s = c->ring[c->calls++ % RING];
     if (s.used) SAPS_HIP(c, hipEventSynchronize(s.done));
-    int32_t* h = s.host;
-    std::memcpy(h, peer, sizeof(int32_t) * c->n);
-    int32_t* units = h + c->n;
-    int32_t u = 0;
+    int32_t* units = s.host;
+    int32_t k = 0;
     for (int32_t i = 0; i < c->n; ++i) {
-        if (peer[i] >= i) { units[2 * u] = i; units[2 * u + 1] = peer[i]; ++u; }
+        if (peer[i] >= i) { units[2 * k] = i; units[2 * k + 1] = peer[i]; ++k; }
     }
-    *n_units = u;
-    SAPS_HIP(c, hipMemcpyAsync(c->d_match, h, sizeof(int32_t) * (size_t)(c->n + 2 * u), hipMemcpyHostToDevice, c->stream));
+    SAPS_HIP(c, hipMemcpyAsync(c->d_match, units, sizeof(int32_t) * 2 * (size_t)u, hipMemcpyHostToDevice, c->stream));
     SAPS_HIP(c, hipEventRecord(s.done, c->stream));
     s.used = true;
+    U->dev = c->d_match;
     return SAPS_OK;
 }
+
+uint32_t tile_blocks(const saps_ctx* c);
 
 constexpr size_t MAX_PROFILE_RECORDS = 4096;
 
@@ -141,13 +155,15 @@ void profile_mark(saps_ctx* c, bool second) {
 
 // K1 + K2: per-tile counts, exclusive tile bases, K and the capacity flag.
 saps_status enqueue_count_scan(saps_ctx* c, const MaskParams& P, int64_t* K_user) {
-    if (c->ntiles > 0)
-        hipLaunchKernelGGL(mask_count_kernel, dim3(c->ntiles), dim3(BLOCK), 0, c->stream, P, c->d_tile);
-    hipLaunchKernelGGL(tile_scan_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_tile, c->ntiles, c->msg_ld,
+    if (c->ngroups > 0)
+        hipLaunchKernelGGL(mask_count_kernel, dim3(c->ngroups), dim3(64 * GROUP), 0, c->stream, P, c->ntiles, c->d_tile, c->d_grp);
+    hipLaunchKernelGGL(group_scan_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_grp, c->ngroups, c->msg_ld,
                        c->d_K, K_user, c->d_flag);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;
 }
+
+uint32_t tile_blocks(const saps_ctx* c) { return (c->ntiles + WAVES - 1) / WAVES; }
 
 uint32_t list_grid_x(const saps_ctx* c) {
     const int64_t b = (c->msg_ld + BLOCK - 1) / BLOCK;
@@ -155,25 +171,25 @@ uint32_t list_grid_x(const saps_ctx* c) {
 }
 
 template <int MODE, int PPB>
-void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, dim3 grid) {
+void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, dim3 grid) {
     if (c->nontemporal)
-        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true>), grid, dim3(BLOCK), 0, c->stream, P, A);
+        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true>), grid, dim3(BLOCK), 0, c->stream, P, A, U);
     else
-        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false>), grid, dim3(BLOCK), 0, c->stream, P, A);
+        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false>), grid, dim3(BLOCK), 0, c->stream, P, A, U);
 }
 
 template <int MODE>
-void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A) {
+void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U) {
     int ppb = c->ppb;
-    const uint32_t gx = c->xcd_remap ? 8u * ((c->ntiles + 7u) / 8u) : c->ntiles;
+    const uint32_t nblk = tile_blocks(c);
+    const uint32_t gx = c->xcd_remap ? 8u * ((nblk + 7u) / 8u) : nblk;
     A.xcd_remap = c->xcd_remap;
     const dim3 grid(gx, (uint32_t)((A.n_units + ppb - 1) / ppb));
     switch (ppb) {
-        case 1: launch_fused_nt<MODE, 1>(c, P, A, grid); break;
-        case 2: launch_fused_nt<MODE, 2>(c, P, A, grid); break;
-        case 4: launch_fused_nt<MODE, 4>(c, P, A, grid); break;
-        case 8: launch_fused_nt<MODE, 8>(c, P, A, grid); break;
-        default: launch_fused_nt<MODE, 16>(c, P, A, grid); break;
+        case 1: launch_fused_nt<MODE, 1>(c, P, A, U, grid); break;
+        case 2: launch_fused_nt<MODE, 2>(c, P, A, U, grid); break;
+        case 4: launch_fused_nt<MODE, 4>(c, P, A, U, grid); break;
+        default: launch_fused_nt<MODE, 8>(c, P, A, U, grid); break;
     }
 }
 
@@ -213,6 +229,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
     c->n = L->n; c->N = L->N; c->ld = L->ld; c->msg_ld = msg_ld;
     c->stream = (hipStream_t)hip_stream;
     c->ntiles = (uint32_t)((L->N + TILE - 1) / TILE);
+    c->ngroups = (c->ntiles + GROUP - 1) / GROUP;
     c->n_seg = (int32_t)seg_T.size();
     c->T0 = seg_T[0];
     c->density = L->N > 0 ? expK / (double)L->N : 0.0;
@@ -222,12 +239,13 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
     chk(hipMalloc(&c->d_seg_end, sizeof(uint32_t) * seg_end.size()));
     chk(hipMalloc(&c->d_seg_T, sizeof(uint64_t) * seg_T.size()));
     chk(hipMalloc(&c->d_tile, sizeof(uint32_t) * ((size_t)c->ntiles + 1)));
+    chk(hipMalloc(&c->d_grp, sizeof(uint32_t) * ((size_t)c->ngroups + 1)));
     chk(hipMalloc(&c->d_K, sizeof(int64_t)));
     chk(hipMalloc(&c->d_flag, sizeof(int32_t)));
     chk(hipMalloc(&c->d_idx, sizeof(uint32_t) * (size_t)std::max<int64_t>(msg_ld, 4)));
-    chk(hipMalloc(&c->d_match, sizeof(int32_t) * 3 * (size_t)c->n));
+    chk(hipMalloc(&c->d_match, sizeof(int32_t) * 2 * (size_t)c->n));
     for (int r = 0; r < RING; ++r) {
-        chk(hipHostMalloc(&c->ring[r].host, sizeof(int32_t) * 3 * (size_t)c->n, hipHostMallocDefault));
+        chk(hipHostMalloc(&c->ring[r].host, sizeof(int32_t) * 2 * (size_t)c->n, hipHostMallocDefault));
         chk(hipEventCreateWithFlags(&c->ring[r].done, hipEventDisableTiming));
     }
     if (e == hipSuccess) chk(hipMemcpy(c->d_seg_end, seg_end.data(), sizeof(uint32_t) * seg_end.size(), hipMemcpyHostToDevice));
@@ -246,7 +264,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
 saps_status saps_destroy(saps_ctx* c) {
     if (!c) return SAPS_EINVAL;
     (void)hipStreamSynchronize(c->stream);
-    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_tile); (void)hipFree(c->d_K);
+    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_tile); (void)hipFree(c->d_grp); (void)hipFree(c->d_K);
     (void)hipFree(c->d_flag); (void)hipFree(c->d_idx); (void)hipFree(c->d_match);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (int r = 0; r < RING; ++r) {
@@ -261,7 +279,7 @@ saps_status saps_set_tuning(saps_ctx* c, int32_t knob, int32_t value) {
     if (!c) return SAPS_EINVAL;
     switch (knob) {
         case SAPS_TUNE_PAIRS_PER_BLOCK:
-            if (value != 1 && value != 2 && value != 4 && value != 8 && value != 16) return fail(c, SAPS_EINVAL, "pairs per block");
+            if (value != 1 && value != 2 && value != 4 && value != 8) return fail(c, SAPS_EINVAL, "pairs per block");
             c->ppb = value; return SAPS_OK;
         case SAPS_TUNE_XCD_REMAP:
             if (value != 0 && value != 1) return fail(c, SAPS_EINVAL, "xcd remap");
@@ -307,7 +325,7 @@ saps_status saps_mask_compact(saps_ctx* c, const float* X, uint64_t seed, uint64
     saps_status s = enqueue_count_scan(c, P, K_dev);
     if (s) return s;
     if (c->ntiles == 0) return SAPS_OK;
-    hipLaunchKernelGGL(idx_scatter_kernel, dim3(c->ntiles), dim3(BLOCK), 0, c->stream, P, c->d_tile, c->d_K, c->msg_ld, idx);
+    hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, c->d_grp, c->d_tile, c->d_K, c->msg_ld, idx);
     hipLaunchKernelGGL(compact_values_kernel, dim3(list_grid_x(c), (uint32_t)c->n), dim3(BLOCK), 0, c->stream,
                        X, c->ld, idx, c->d_K, c->msg_ld, msg, c->msg_ld);
     SAPS_HIP(c, hipGetLastError());
@@ -322,11 +340,12 @@ saps_status saps_merge(saps_ctx* c, float* X, const int32_t* peer, const uint32_
         return fail(c, SAPS_EINVAL, "misaligned pointer");
     if (!matching_ok(c->n, peer)) return fail(c, SAPS_EMATCH, "peer[] is not an involution of [0, n)");
     int32_t n_units = 0;
-    saps_status s = upload_matching(c, peer, &n_units);
+    Units U;
+    saps_status s = make_units(c, peer, &U, &n_units);
     if (s) return s;
     if (c->N == 0) return SAPS_OK;
-    hipLaunchKernelGGL(merge_kernel, dim3(list_grid_x(c), (uint32_t)c->n), dim3(BLOCK), 0, c->stream,
-                       X, c->ld, c->d_match, idx, msg, c->msg_ld, K_dev, c->msg_ld);
+    hipLaunchKernelGGL(merge_kernel, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
+                       X, c->ld, U, idx, msg, c->msg_ld, K_dev, c->msg_ld);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;
 }
@@ -342,7 +361,8 @@ saps_status saps_round(saps_ctx* c, float* X, const float* G, float* V, float lr
     if (G && !V && mu != 0.0f) return fail(c, SAPS_EINVAL, "momentum needs V");
     if (!matching_ok(c->n, peer)) return fail(c, SAPS_EMATCH, "peer[] is not an involution of [0, n)");
     int32_t n_units = 0;
-    saps_status s = upload_matching(c, peer, &n_units);
+    Units U;
+    saps_status s = make_units(c, peer, &U, &n_units);
     if (s) return s;
     const MaskParams P = mask_params(c, seed, round);
     s = enqueue_count_scan(c, P, K_dev);
@@ -351,26 +371,26 @@ saps_status saps_round(saps_ctx* c, float* X, const float* G, float* V, float lr
 
     FusedArgs A;
     A.X = X; A.G = G; A.V = V; A.ld = c->ld;
-    A.units = c->d_match + c->n; A.n_units = n_units;
+    A.n_units = n_units;
     A.lr = lr; A.mu = mu;
-    A.tile_base = c->d_tile; A.K_int = c->d_K; A.cap = c->msg_ld;
+    A.grp_base = c->d_grp; A.tile_cnt = c->d_tile; A.K_int = c->d_K; A.cap = c->msg_ld;
     A.idx = idx; A.msg = msg; A.msg_ld = c->msg_ld;
     A.ntiles = c->ntiles; A.xcd_remap = 0;
 
     if (G) {
         profile_mark(c, false);
-        if (V) launch_fused<0>(c, P, A); else launch_fused<1>(c, P, A);
+        if (V) launch_fused<0>(c, P, A, U); else launch_fused<1>(c, P, A, U);
         profile_mark(c, true);
     } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 0.125)) {
         profile_mark(c, false);
-        launch_fused<2>(c, P, A);                     // dense masks: walk the tiles
+        launch_fused<2>(c, P, A, U);                   // dense masks: walk the tiles
         profile_mark(c, true);
     } else {
         uint32_t* list = idx ? idx : c->d_idx;        // sparse masks: go through the index list
-        hipLaunchKernelGGL(idx_scatter_kernel, dim3(c->ntiles), dim3(BLOCK), 0, c->stream, P, c->d_tile, c->d_K, c->msg_ld, list);
+        hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, c->d_grp, c->d_tile, c->d_K, c->msg_ld, list);
         profile_mark(c, false);
         hipLaunchKernelGGL(exchange_list_kernel, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
-                           X, c->ld, c->d_match + c->n, list, c->d_K, c->msg_ld, msg, c->msg_ld);
+                           X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);
         profile_mark(c, true);
     }
     SAPS_HIP(c, hipGetLastError());

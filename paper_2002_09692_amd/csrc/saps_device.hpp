@@ -1,9 +1,10 @@
 // Device kernels of the SAPS-PSGD round for gfx950 (wave64).  Included by saps_api.hip only.
 //
 // Work decomposition shared by all mask-driven kernels: the coordinate axis is cut into
-// tiles of TILE = 1024 coordinates; a workgroup of 256 lanes owns one tile and lane l owns
-// the four coordinates 4*(256*tile + l) .. +3, which are exactly one Philox4x32-10 block,
-// one 16-byte access per row, and one nibble of mask bits.
+// tiles of TILE = 256 coordinates; one wave owns one tile and lane l owns the four
+// coordinates 4*(64*tile + l) .. +3, which are exactly one Philox4x32-10 block, one 16-byte
+// access per row, and one nibble of mask bits.  Packed positions inside a tile come from
+// wave ballots alone, so no kernel needs LDS or a barrier.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -12,8 +13,10 @@
 namespace saps {
 
 constexpr int BLOCK = 256;          // lanes per workgroup (4 waves)
-constexpr int TILE = BLOCK * 4;     // coordinates per tile
 constexpr int WAVES = BLOCK / 64;
+constexpr int TILE = 64 * 4;        // coordinates per tile: one wave, one Philox block per lane
+constexpr int GROUP = 16;           // tiles per group: the counting kernel's workgroup of 16 waves
+constexpr int MAX_INLINE_UNITS = 128;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
@@ -85,9 +88,8 @@ __device__ __forceinline__ uint32_t mask4(const MaskParams& P, uint32_t q, int s
 }
 
 // Exclusive prefix (in ascending coordinate order) of the kept coordinates in front of this
-// lane's nibble inside the workgroup, and the workgroup total.  One call per kernel: wave
-// ballots give the in-wave part, one LDS word per wave the rest.
-__device__ __forceinline__ uint32_t block_prefix(uint32_t m, uint32_t* wave_tot /* LDS[WAVES] */, uint32_t& total) {
+// lane's nibble inside its wave tile, and the tile total, from four ballots.
+__device__ __forceinline__ uint32_t wave_prefix(uint32_t m, uint32_t& total) {
     uint32_t excl = 0u, wsum = 0u;
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -95,84 +97,122 @@ __device__ __forceinline__ uint32_t block_prefix(uint32_t m, uint32_t* wave_tot 
         excl += __builtin_amdgcn_mbcnt_hi((uint32_t)(b >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)b, 0u));
         wsum += (uint32_t)__popcll(b);
     }
-    const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) wave_tot[wave] = wsum;
-    __syncthreads();
-    uint32_t before = 0u, all = 0u;
-#pragma unroll
-    for (int w = 0; w < WAVES; ++w) {
-        const uint32_t t = wave_tot[w];
-        before += (w < wave) ? t : 0u;
-        all += t;
+    total = wsum;
+    return excl;
+}
+
+// The matching as a list of units (i, p): a matched pair with i < p, or an unmatched worker
+// with i == p.  Small lists travel inside the kernel arguments (no upload, no extra launch);
+// longer ones are read from device memory.
+struct Units {
+    const int32_t* dev;                    // 2 ints per unit, or null when the list is inline
+    uint32_t packed[MAX_INLINE_UNITS];     // i | p << 16
+};
+
+__device__ __forceinline__ void unit_at(const Units& U, int u, int32_t& i, int32_t& p) {
+    if (U.dev) {
+        i = U.dev[2 * u]; p = U.dev[2 * u + 1];
+    } else {
+        const uint32_t w = U.packed[u];
+        i = (int32_t)(w & 0xFFFFu); p = (int32_t)(w >> 16);
     }
-    total = all;
-    return excl + before;
 }
 
-// ------------------------------------------------------------------ K1: per-tile counts
-__global__ __launch_bounds__(BLOCK) void mask_count_kernel(MaskParams P, uint32_t* __restrict__ tile_cnt) {
-    __shared__ uint32_t wave_tot[WAVES];
-    const uint32_t tile = blockIdx.x;
-    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile * (uint32_t)TILE) : 0;
-    const uint32_t m = mask4(P, tile * BLOCK + threadIdx.x, seg0);
-    uint32_t total;
-    (void)block_prefix(m, wave_tot, total);
-    if (threadIdx.x == 0) tile_cnt[tile] = total;
+// ------------------------------------------------ K1: per-tile and per-group kept counts
+// One workgroup of 16 waves per group of 16 tiles.
+__global__ __launch_bounds__(64 * GROUP) void mask_count_kernel(MaskParams P, uint32_t ntiles,
+                                                                uint32_t* __restrict__ tile_cnt,
+                                                                uint32_t* __restrict__ grp_cnt) {
+    __shared__ uint32_t wsum[GROUP];
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t tile = blockIdx.x * GROUP + wave;
+    uint32_t total = 0u;
+    if (tile < ntiles) {
+        const int seg0 = (P.n_seg > 1) ? first_segment(P, tile * (uint32_t)TILE) : 0;
+        const uint32_t m = mask4(P, tile * 64u + (threadIdx.x & 63u), seg0);
+        (void)wave_prefix(m, total);
+        if ((threadIdx.x & 63u) == 0u) tile_cnt[tile] = total;
+    }
+    if ((threadIdx.x & 63u) == 0u) wsum[wave] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t g = 0u;
+#pragma unroll
+        for (int w = 0; w < GROUP; ++w) g += wsum[w];
+        grp_cnt[blockIdx.x] = g;
+    }
 }
 
-// ------------------------------------------- K2: counts -> exclusive tile bases, K, flag
-// One workgroup of 1024 lanes; lane t scans the contiguous chunk [t*L, (t+1)*L).
-__global__ __launch_bounds__(1024) void tile_scan_kernel(uint32_t* __restrict__ tile_cnt, uint32_t ntiles,
-                                                         int64_t cap, int64_t* __restrict__ K_int,
-                                                         int64_t* __restrict__ K_user, int32_t* __restrict__ flag) {
+// ------------------------------------ K2: group counts -> exclusive group bases, K, flag
+// One workgroup of 1024 lanes walks the group counts 4096 at a time with a running carry.
+__global__ __launch_bounds__(1024) void group_scan_kernel(uint32_t* __restrict__ grp, uint32_t ngroups,
+                                                          int64_t cap, int64_t* __restrict__ K_int,
+                                                          int64_t* __restrict__ K_user, int32_t* __restrict__ flag) {
     __shared__ uint32_t wsum[16];
     const uint32_t t = threadIdx.x;
-    const uint32_t L = (ntiles + 1023u) / 1024u;
-    const uint32_t lo = min(t * L, ntiles), hi = min(lo + L, ntiles);
-    uint32_t s = 0u;
-    for (uint32_t k = lo; k < hi; ++k) s += tile_cnt[k];
-    // inclusive scan of s over the 1024 lanes
-    uint32_t inc = s;
+    uint32_t carry = 0u;
+    for (uint32_t base = 0u; base < ngroups; base += 4096u) {
+        const uint32_t k0 = base + 4u * t;
+        uint32_t c[4];
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const uint32_t o = __shfl_up(inc, d, 64);
-        if ((int)(t & 63u) >= d) inc += o;
-    }
-    if ((t & 63u) == 63u) wsum[t >> 6] = inc;
-    __syncthreads();
-    uint32_t before = 0u, all = 0u;
+        for (int r = 0; r < 4; ++r) c[r] = (k0 + r < ngroups) ? grp[k0 + r] : 0u;
+        const uint32_t s = c[0] + c[1] + c[2] + c[3];
+        uint32_t inc = s;
 #pragma unroll
-    for (int w = 0; w < 16; ++w) {
-        const uint32_t v = wsum[w];
-        before += (w < (int)(t >> 6)) ? v : 0u;
-        all += v;
-    }
-    uint32_t run = before + inc - s;
-    for (uint32_t k = lo; k < hi; ++k) {
-        const uint32_t c = tile_cnt[k];
-        tile_cnt[k] = run;
-        run += c;
+        for (int d = 1; d < 64; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d, 64);
+            if ((int)(t & 63u) >= d) inc += o;
+        }
+        if ((t & 63u) == 63u) wsum[t >> 6] = inc;
+        __syncthreads();
+        uint32_t before = 0u, all = 0u;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const uint32_t v = wsum[w];
+            before += (w < (int)(t >> 6)) ? v : 0u;
+            all += v;
+        }
+        uint32_t run = carry + before + inc - s;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if (k0 + r < ngroups) grp[k0 + r] = run;
+            run += c[r];
+        }
+        carry += all;
+        __syncthreads();
     }
     if (t == 0) {
-        tile_cnt[ntiles] = all;
-        *K_int = (int64_t)all;
-        if (K_user) *K_user = (int64_t)all;
-        if ((int64_t)all > cap) *flag = 1;
+        *K_int = (int64_t)carry;
+        if (K_user) *K_user = (int64_t)carry;
+        if ((int64_t)carry > cap) *flag = 1;
     }
+}
+
+// Packed position of the first kept coordinate of a tile: its group's base plus the counts of
+// the tiles in front of it inside the group (at most 15 words, one per lane, summed by swaps).
+__device__ __forceinline__ uint32_t tile_base_of(const uint32_t* __restrict__ grp_base,
+                                                 const uint32_t* __restrict__ tile_cnt, uint32_t tile) {
+    const uint32_t g = tile / GROUP, r = tile % GROUP, lane = threadIdx.x & 63u;
+    uint32_t v = (lane < r) ? tile_cnt[g * GROUP + lane] : 0u;
+#pragma unroll
+    for (int d = 1; d < GROUP; d <<= 1) v += __shfl_xor(v, d, 64);
+    return grp_base[g] + __builtin_amdgcn_readfirstlane(v);
 }
 
 // --------------------------------------------------------- K3: ascending index list idx
-__global__ __launch_bounds__(BLOCK) void idx_scatter_kernel(MaskParams P, const uint32_t* __restrict__ tile_base,
+__global__ __launch_bounds__(BLOCK) void idx_scatter_kernel(MaskParams P, uint32_t ntiles,
+                                                            const uint32_t* __restrict__ grp_base,
+                                                            const uint32_t* __restrict__ tile_cnt,
                                                             const int64_t* __restrict__ K_int, int64_t cap,
                                                             uint32_t* __restrict__ idx) {
-    __shared__ uint32_t wave_tot[WAVES];
     if (*K_int > cap) return;
-    const uint32_t tile = blockIdx.x;
+    const uint32_t tile = blockIdx.x * WAVES + (threadIdx.x >> 6);
+    if (tile >= ntiles) return;
     const int seg0 = (P.n_seg > 1) ? first_segment(P, tile * (uint32_t)TILE) : 0;
-    const uint32_t q = tile * BLOCK + threadIdx.x;
+    const uint32_t q = tile * 64u + (threadIdx.x & 63u);
     const uint32_t m = mask4(P, q, seg0);
     uint32_t total;
-    uint32_t pos = tile_base[tile] + block_prefix(m, wave_tot, total);
+    uint32_t pos = tile_base_of(grp_base, tile_cnt, tile) + wave_prefix(m, total);
     if (m) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
@@ -239,30 +279,36 @@ __global__ __launch_bounds__(BLOCK) void compact_values_kernel(const float* __re
 }
 
 // -------------------------------------------------- K6: average the two packed messages
-__global__ __launch_bounds__(BLOCK) void merge_kernel(float* __restrict__ X, int64_t ld, const int32_t* __restrict__ peer,
+__global__ __launch_bounds__(BLOCK) void merge_kernel(float* __restrict__ X, int64_t ld, Units U,
                                                       const uint32_t* __restrict__ idx, const float* __restrict__ msg,
                                                       int64_t msg_ld, const int64_t* __restrict__ K_dev, int64_t cap) {
     const int64_t K = *K_dev;
     if (K > cap || K < 0) return;
-    const int32_t i = blockIdx.y, p = peer[i];
+    int32_t i, p;
+    unit_at(U, blockIdx.y, i, p);
     if (p == i) return;
-    float* x = X + (int64_t)i * ld;
+    float* xi = X + (int64_t)i * ld;
+    float* xp = X + (int64_t)p * ld;
     const float* a = msg + (int64_t)i * msg_ld;
     const float* b = msg + (int64_t)p * msg_ld;
-    for (int64_t k = (int64_t)blockIdx.x * BLOCK + threadIdx.x; k < K; k += (int64_t)gridDim.x * BLOCK)
-        x[idx[k]] = (a[k] + b[k]) * 0.5f;
+    for (int64_t k = (int64_t)blockIdx.x * BLOCK + threadIdx.x; k < K; k += (int64_t)gridDim.x * BLOCK) {
+        const float avg = (a[k] + b[k]) * 0.5f;
+        const uint32_t j = idx[k];
+        xi[j] = avg;
+        xp[j] = avg;
+    }
 }
 
 // -------------------------- K8: exchange-only round through the index list (sparse masks)
 // unit u = (i, p): a matched pair with i < p, or an unmatched worker with i == p.
-__global__ __launch_bounds__(BLOCK) void exchange_list_kernel(float* __restrict__ X, int64_t ld,
-                                                              const int32_t* __restrict__ units,
+__global__ __launch_bounds__(BLOCK) void exchange_list_kernel(float* __restrict__ X, int64_t ld, Units U,
                                                               const uint32_t* __restrict__ idx,
                                                               const int64_t* __restrict__ K_int, int64_t cap,
                                                               float* __restrict__ msg, int64_t msg_ld) {
     const int64_t K = *K_int;
     if (K > cap) return;
-    const int32_t i = units[2 * blockIdx.y], p = units[2 * blockIdx.y + 1];
+    int32_t i, p;
+    unit_at(U, blockIdx.y, i, p);
     float* xi = X + (int64_t)i * ld;
     float* xp = X + (int64_t)p * ld;
     for (int64_t k = (int64_t)blockIdx.x * BLOCK + threadIdx.x; k < K; k += (int64_t)gridDim.x * BLOCK) {
@@ -281,128 +327,170 @@ __global__ __launch_bounds__(BLOCK) void exchange_list_kernel(float* __restrict_
 
 // ------------------------------------------------------------------ K7: fused dense round
 // MODE 0: update with momentum buffer, 1: update without buffer, 2: no update (exchange only).
-// Grid: x = tiles (optionally remapped so that each XCD walks one contiguous range),
-//       y = chunks of PPB units.  The mask nibble and the packed position of a lane's four
-//       coordinates are computed once and reused for all PPB units of the chunk.
+// Grid: x = workgroups of 4 wave tiles (optionally remapped so that each XCD walks one
+//       contiguous range), y = chunks of PPB units.  The mask nibble and the packed position
+//       of a lane's four coordinates are computed once and reused for all PPB units of the
+//       chunk.  Waves never talk to each other: no LDS, no barrier.
 struct FusedArgs {
     float* X; const float* G; float* V;
     int64_t ld;
-    const int32_t* units; int32_t n_units;
+    int32_t n_units;
     float lr, mu;
-    const uint32_t* tile_base; const int64_t* K_int; int64_t cap;
+    const uint32_t* grp_base; const uint32_t* tile_cnt; const int64_t* K_int; int64_t cap;
     uint32_t* idx; float* msg; int64_t msg_ld;
     uint32_t ntiles; int32_t xcd_remap;
 };
 
-template <int MODE, int PPB, bool NT>
-__global__ __launch_bounds__(BLOCK) void fused_round_kernel(MaskParams P, FusedArgs A) {
-    __shared__ uint32_t wave_tot[WAVES];
-    if (*A.K_int > A.cap) return;
-    uint32_t tile = blockIdx.x;
-    if (A.xcd_remap) {
-        // workgroups are dealt round-robin to the 8 XCDs; give XCD x the tiles [x*per, (x+1)*per)
-        const uint32_t per = (A.ntiles + 7u) >> 3;
-        tile = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
-        if (tile >= A.ntiles) return;
+// The six 16-byte operands of one unit (matched pair i,p or single worker i) at one lane.
+struct Operands { f4 xi, gi, vi, xp, gp, vp; };
+
+template <int MODE, bool NT>
+__device__ __forceinline__ Operands load_unit(const FusedArgs& A, int32_t i, int32_t p, uint32_t j0, uint32_t nval) {
+    const f4 z = {0.f, 0.f, 0.f, 0.f};
+    Operands o = {z, z, z, z, z, z};
+    const bool paired = (p != i);
+    const int64_t ei = (int64_t)i * A.ld + j0, ep = (int64_t)p * A.ld + j0;
+    if (nval == 4u) {
+        o.xi = ld4<NT>(A.X + ei);
+        if (MODE != 2) o.gi = ld4<NT>(A.G + ei);
+        if (MODE == 0) o.vi = ld4<NT>(A.V + ei);
+        if (paired) {
+            o.xp = ld4<NT>(A.X + ep);
+            if (MODE != 2) o.gp = ld4<NT>(A.G + ep);
+            if (MODE == 0) o.vp = ld4<NT>(A.V + ep);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            if ((uint32_t)r < nval) {
+                o.xi[r] = A.X[ei + r];
+                if (MODE != 2) o.gi[r] = A.G[ei + r];
+                if (MODE == 0) o.vi[r] = A.V[ei + r];
+                if (paired) {
+                    o.xp[r] = A.X[ep + r];
+                    if (MODE != 2) o.gp[r] = A.G[ep + r];
+                    if (MODE == 0) o.vp[r] = A.V[ep + r];
+                }
+            }
+        }
     }
-    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile * (uint32_t)TILE) : 0;
-    const uint32_t q = tile * BLOCK + threadIdx.x;
+    return o;
+}
+
+// Local step, message write, averaging and write-back of one unit at one lane.
+template <int MODE, bool NT>
+__device__ __forceinline__ void finish_unit(const FusedArgs& A, Operands& o, int32_t i, int32_t p, uint32_t j0,
+                                            uint32_t nval, uint32_t m, uint32_t pos0) {
+    const bool paired = (p != i);
+    const int64_t ei = (int64_t)i * A.ld + j0, ep = (int64_t)p * A.ld + j0;
+    if (MODE != 2) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float x = o.xi[r], v = o.vi[r];
+            step1<MODE == 0>(x, o.gi[r], v, A.lr, A.mu);
+            o.xi[r] = x; o.vi[r] = v;
+            x = o.xp[r]; v = o.vp[r];
+            step1<MODE == 0>(x, o.gp[r], v, A.lr, A.mu);
+            o.xp[r] = x; o.vp[r] = v;
+        }
+    }
+    if (m) {
+        uint32_t pos = pos0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if ((m >> r) & 1u) {
+                if (A.msg) {
+                    A.msg[(int64_t)i * A.msg_ld + pos] = o.xi[r];
+                    if (paired) A.msg[(int64_t)p * A.msg_ld + pos] = o.xp[r];
+                }
+                ++pos;
+                if (paired) {
+                    const float avg = (o.xi[r] + o.xp[r]) * 0.5f;
+                    o.xi[r] = avg; o.xp[r] = avg;
+                }
+            }
+        }
+    }
+    if (nval == 4u) {
+        if (MODE != 2 || paired) st4<NT>(A.X + ei, o.xi);
+        if (MODE == 0) st4<NT>(A.V + ei, o.vi);
+        if (paired) {
+            st4<NT>(A.X + ep, o.xp);
+            if (MODE == 0) st4<NT>(A.V + ep, o.vp);
+        }
+    } else {
+#pragma unroll
+        for (int r = 0; r < 3; ++r) {
+            if ((uint32_t)r < nval) {
+                if (MODE != 2 || paired) A.X[ei + r] = o.xi[r];
+                if (MODE == 0) A.V[ei + r] = o.vi[r];
+                if (paired) {
+                    A.X[ep + r] = o.xp[r];
+                    if (MODE == 0) A.V[ep + r] = o.vp[r];
+                }
+            }
+        }
+    }
+}
+
+template <int MODE, int PPB, bool NT>
+__global__ __launch_bounds__(BLOCK) void fused_round_kernel(MaskParams P, FusedArgs A, Units U) {
+    uint32_t blk = blockIdx.x;
+    if (A.xcd_remap) {
+        // workgroups are dealt round-robin to the 8 XCDs; give XCD x the range [x*per, (x+1)*per)
+        const uint32_t nblk = (A.ntiles + WAVES - 1) / WAVES;
+        const uint32_t per = (nblk + 7u) >> 3;
+        blk = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
+    }
+    const uint32_t tile = blk * WAVES + (threadIdx.x >> 6);          // wave-uniform
+    if (tile >= A.ntiles) return;
+    const uint32_t q = tile * 64u + (threadIdx.x & 63u);
     const uint32_t j0 = q << 2;
+    const bool live = j0 < P.N;
+    const uint32_t nval = live ? min(4u, P.N - j0) : 0u;
+    const int u_lo = blockIdx.y * PPB;
+    const int u_hi = min(u_lo + PPB, A.n_units);
+    const int64_t K = *A.K_int;
+
+    // the first unit's operands are requested before the mask arithmetic so that the Philox
+    // rounds run while the loads are in flight
+    int32_t i, p;
+    unit_at(U, u_lo, i, p);
+    Operands cur;
+    if (MODE != 2 && live) cur = load_unit<MODE, NT>(A, i, p, j0, nval);
+
+    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile * (uint32_t)TILE) : 0;
     const uint32_t m = mask4(P, q, seg0);
     uint32_t total;
-    const uint32_t pos0 = A.tile_base[tile] + block_prefix(m, wave_tot, total);
-    if (MODE == 2 && total == 0u) return;                    // nothing of this tile is exchanged
+    const uint32_t pos0 = tile_base_of(A.grp_base, A.tile_cnt, tile) + wave_prefix(m, total);
+    if (K > A.cap) return;                                            // nothing may be written
+    if (MODE == 2 && total == 0u) return;                             // nothing of this tile is exchanged
     if (blockIdx.y == 0 && A.idx && m) {
         uint32_t pos = pos0;
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             if ((m >> r) & 1u) A.idx[pos++] = j0 + r;
     }
-    if (j0 >= P.N) return;
-    const bool full = (P.N - j0) >= 4u;
-    const uint32_t nval = full ? 4u : (P.N - j0);
-    const int u_lo = blockIdx.y * PPB;
-    const int u_hi = min(u_lo + PPB, A.n_units);
-    if (MODE == 2 && m == 0u) return;                        // this lane exchanges nothing
-
+    if (!live) return;
+    if (MODE == 2) {
+        if (m == 0u) return;                                          // this lane exchanges nothing
+        for (int u = u_lo; u < u_hi; ++u) {
+            unit_at(U, u, i, p);
+            cur = load_unit<MODE, NT>(A, i, p, j0, nval);
+            finish_unit<MODE, NT>(A, cur, i, p, j0, nval, m, pos0);
+        }
+        return;
+    }
 #pragma unroll 1
     for (int u = u_lo; u < u_hi; ++u) {
-        const int32_t i = A.units[2 * u], p = A.units[2 * u + 1];
-        const bool paired = (p != i);
-        const int64_t ei = (int64_t)i * A.ld + j0, ep = (int64_t)p * A.ld + j0;
-        f4 xi = {0.f, 0.f, 0.f, 0.f}, gi = xi, vi = xi, xp = xi, gp = xi, vp = xi;
-        if (full) {
-            xi = ld4<NT>(A.X + ei);
-            if (MODE != 2) gi = ld4<NT>(A.G + ei);
-            if (MODE == 0) vi = ld4<NT>(A.V + ei);
-            if (paired) {
-                xp = ld4<NT>(A.X + ep);
-                if (MODE != 2) gp = ld4<NT>(A.G + ep);
-                if (MODE == 0) vp = ld4<NT>(A.V + ep);
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                if ((uint32_t)r < nval) {
-                    xi[r] = A.X[ei + r];
-                    if (MODE != 2) gi[r] = A.G[ei + r];
-                    if (MODE == 0) vi[r] = A.V[ei + r];
-                    if (paired) {
-                        xp[r] = A.X[ep + r];
-                        if (MODE != 2) gp[r] = A.G[ep + r];
-                        if (MODE == 0) vp[r] = A.V[ep + r];
-                    }
-                }
-            }
+        Operands nxt;
+        int32_t in = i, pn = p;
+        if (PPB > 1 && u + 1 < u_hi) {
+            unit_at(U, u + 1, in, pn);
+            nxt = load_unit<MODE, NT>(A, in, pn, j0, nval);
         }
-        if (MODE != 2) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                float x = xi[r], v = vi[r];
-                step1<MODE == 0>(x, gi[r], v, A.lr, A.mu);
-                xi[r] = x; vi[r] = v;
-                x = xp[r]; v = vp[r];
-                step1<MODE == 0>(x, gp[r], v, A.lr, A.mu);
-                xp[r] = x; vp[r] = v;
-            }
-        }
-        if (m) {
-            uint32_t pos = pos0;
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if ((m >> r) & 1u) {
-                    if (A.msg) {
-                        A.msg[(int64_t)i * A.msg_ld + pos] = xi[r];
-                        if (paired) A.msg[(int64_t)p * A.msg_ld + pos] = xp[r];
-                    }
-                    ++pos;
-                    if (paired) {
-                        const float avg = (xi[r] + xp[r]) * 0.5f;
-                        xi[r] = avg; xp[r] = avg;
-                    }
-                }
-            }
-        }
-        if (full) {
-            if (MODE != 2 || paired) st4<NT>(A.X + ei, xi);
-            if (MODE == 0) st4<NT>(A.V + ei, vi);
-            if (paired) {
-                st4<NT>(A.X + ep, xp);
-                if (MODE == 0) st4<NT>(A.V + ep, vp);
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 3; ++r) {
-                if ((uint32_t)r < nval) {
-                    if (MODE != 2 || paired) A.X[ei + r] = xi[r];
-                    if (MODE == 0) A.V[ei + r] = vi[r];
-                    if (paired) {
-                        A.X[ep + r] = xp[r];
-                        if (MODE == 0) A.V[ep + r] = vp[r];
-                    }
-                }
-            }
-        }
+        finish_unit<MODE, NT>(A, cur, i, p, j0, nval, m, pos0);
+        if (PPB > 1) { cur = nxt; i = in; p = pn; }
     }
 }
 
