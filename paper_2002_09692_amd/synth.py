@@ -13,6 +13,8 @@ normal draw with an initialisation-like per-tensor scale.
 from __future__ import annotations
 
 import dataclasses
+import os
+from concurrent.futures import ThreadPoolExecutor
 from typing import List, Optional, Sequence, Tuple
 
 import numpy as np
@@ -178,16 +180,27 @@ def workload(name: str) -> Workload:
 # --------------------------------------------------------------------------- values
 def _fill_rows(out: np.ndarray, N: int, seg_off: np.ndarray, seg_std: Sequence[float],
                seed: Sequence[int]) -> None:
-    """Row i of out[:, :N] gets independent N(0, std_seg^2) draws; padding stays as is."""
+    """Row i of out[:, :N] gets independent N(0, std_seg^2) draws; padding stays as is.
+    Every row has its own generator seeded by (seed..., i), so the result does not depend
+    on how the rows are spread over threads."""
     stdvec = np.repeat(np.asarray(seg_std, dtype=np.float32), np.diff(seg_off)) if len(seg_std) > 1 else None
-    for i in range(out.shape[0]):
+
+    def one(i: int) -> None:
         rng = np.random.default_rng(list(seed) + [i])
-        row = rng.standard_normal(N, dtype=np.float32)
+        row = out[i, :N]
+        rng.standard_normal(N, dtype=np.float32, out=row)
         if stdvec is not None:
             row *= stdvec
         else:
             row *= np.float32(seg_std[0])
-        out[i, :N] = row
+
+    workers = min(8, os.cpu_count() or 1, out.shape[0])
+    if workers > 1 and out.shape[0] * N > (1 << 22):
+        with ThreadPoolExecutor(workers) as ex:
+            list(ex.map(one, range(out.shape[0])))
+    else:
+        for i in range(out.shape[0]):
+            one(i)
 
 
 def make_models(wl: Workload, ld: Optional[int] = None, pad_value: float = 0.0,
