@@ -50,7 +50,7 @@ struct saps_ctx {
     Slot ring[RING];
     uint64_t calls = 0;
     // launch-shape knobs
-    int32_t ppb = 1, xcd_remap = 0, nontemporal = 1, exchange_path = 0;
+    int32_t ppb = 1, xcd_remap = 0, nontemporal = 1, exchange_path = 0, blocks_per_cu = 6;
     // optional event pairs around the dominant kernel of a call
     bool profiling = false;
     std::vector<hipEvent_t> ev_pool;    // 2 events per record, created on demand
@@ -133,6 +133,14 @@ saps_status make_units(saps_ctx* c, const int32_t* peer, Units* U, int32_t* n_un
 
 uint32_t tile_blocks(const saps_ctx* c);
 
+// The fused round kernel runs fastest with few resident waves per compute unit (fewer DRAM
+// pages open at once: measured best at 12 waves).  Residency is capped by giving each
+// workgroup a slice of the 160 KB LDS that it never touches: 156 KB / blocks leaves room for
+// exactly that many workgroups.
+uint32_t residency_lds_bytes(int32_t blocks_per_cu) {
+    return blocks_per_cu > 0 ? (uint32_t)(156 / blocks_per_cu) * 1024u : 0u;
+}
+
 constexpr size_t MAX_PROFILE_RECORDS = 4096;
 
 // Records an event on the stream if profiling is on; `second` closes the pair opened before.
@@ -172,16 +180,17 @@ uint32_t list_grid_x(const saps_ctx* c) {
 
 template <int MODE, int PPB>
 void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, dim3 grid) {
+    const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(c->blocks_per_cu);
     if (c->nontemporal)
-        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true>), grid, dim3(BLOCK), 0, c->stream, P, A, U);
+        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
     else
-        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false>), grid, dim3(BLOCK), 0, c->stream, P, A, U);
+        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
 }
 
 template <int MODE>
 void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U) {
     int ppb = c->ppb;
-    const uint32_t nblk = tile_blocks(c);
+    const uint32_t nblk = (c->ntiles + FUSED_WAVES - 1) / FUSED_WAVES;
     const uint32_t gx = c->xcd_remap ? 8u * ((nblk + 7u) / 8u) : nblk;
     A.xcd_remap = c->xcd_remap;
     const dim3 grid(gx, (uint32_t)((A.n_units + ppb - 1) / ppb));
@@ -287,6 +296,9 @@ saps_status saps_set_tuning(saps_ctx* c, int32_t knob, int32_t value) {
         case SAPS_TUNE_NONTEMPORAL:
             if (value != 0 && value != 1) return fail(c, SAPS_EINVAL, "nontemporal");
             c->nontemporal = value; return SAPS_OK;
+        case SAPS_TUNE_BLOCKS_PER_CU:
+            if (value != 0 && (value < 3 || value > 16)) return fail(c, SAPS_EINVAL, "blocks per CU");
+            c->blocks_per_cu = value; return SAPS_OK;
         case SAPS_TUNE_EXCHANGE_PATH:
             if (value < 0 || value > 2) return fail(c, SAPS_EINVAL, "exchange path");
             c->exchange_path = value; return SAPS_OK;
@@ -302,13 +314,14 @@ saps_status saps_sgd_step(saps_ctx* c, float* X, const float* G, float* V, float
     const uint32_t gx = (uint32_t)(((c->N + 3) / 4 + BLOCK - 1) / BLOCK);
     const dim3 grid(gx, (uint32_t)c->n);
     const uint32_t N = (uint32_t)c->N;
+    const uint32_t SGD_LDS = residency_lds_bytes(6);          // 6 workgroups of 4 waves per compute unit
     profile_mark(c, false);
     if (V) {
-        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
-        else hipLaunchKernelGGL((sgd_kernel<true, false>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
+        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, dim3(BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
+        else hipLaunchKernelGGL((sgd_kernel<true, false>), grid, dim3(BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
     } else {
-        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<false, true>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
-        else hipLaunchKernelGGL((sgd_kernel<false, false>), grid, dim3(BLOCK), 0, c->stream, X, G, V, c->ld, N, lr, mu);
+        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<false, true>), grid, dim3(BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
+        else hipLaunchKernelGGL((sgd_kernel<false, false>), grid, dim3(BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
     }
     profile_mark(c, true);
     SAPS_HIP(c, hipGetLastError());

@@ -17,6 +17,8 @@ constexpr int WAVES = BLOCK / 64;
 constexpr int TILE = 64 * 4;        // coordinates per tile: one wave, one Philox block per lane
 constexpr int GROUP = 16;           // tiles per group: the counting kernel's workgroup of 16 waves
 constexpr int MAX_INLINE_UNITS = 128;
+constexpr int FUSED_BLOCK = 128;    // lanes per workgroup of the fused round kernel (2 independent waves)
+constexpr int FUSED_WAVES = FUSED_BLOCK / 64;
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
@@ -32,17 +34,20 @@ struct MaskParams {
 };
 
 // Philox4x32-10 (Salmon et al., SC'11): ten rounds, each two 32x32->64 products, a word
-// permutation with key injection, and a Weyl step of the key.
+// permutation with key injection, and a Weyl step of the key.  The products are written as
+// 64-bit multiplies of zero-extended words so that each becomes one v_mad_u64_u32.
 __device__ __forceinline__ void philox4x32_10(uint32_t& c0, uint32_t& c1, uint32_t& c2, uint32_t& c3,
                                               uint32_t k0, uint32_t k1) {
 #pragma unroll
     for (int r = 0; r < 10; ++r) {
-        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
-        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
-        c0 = hi1 ^ c1 ^ k0;
-        c1 = lo1;
-        c2 = hi0 ^ c3 ^ k1;
-        c3 = lo0;
+        const uint64_t p0 = (uint64_t)0xD2511F53u * (uint64_t)c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * (uint64_t)c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
     }
@@ -208,6 +213,7 @@ __global__ __launch_bounds__(BLOCK) void idx_scatter_kernel(MaskParams P, uint32
     if (*K_int > cap) return;
     const uint32_t tile = blockIdx.x * WAVES + (threadIdx.x >> 6);
     if (tile >= ntiles) return;
+    if (tile_cnt[tile] == 0u) return;                    // nothing kept here: no need to redo the Philox block
     const int seg0 = (P.n_seg > 1) ? first_segment(P, tile * (uint32_t)TILE) : 0;
     const uint32_t q = tile * 64u + (threadIdx.x & 63u);
     const uint32_t m = mask4(P, q, seg0);
@@ -327,7 +333,7 @@ __global__ __launch_bounds__(BLOCK) void exchange_list_kernel(float* __restrict_
 
 // ------------------------------------------------------------------ K7: fused dense round
 // MODE 0: update with momentum buffer, 1: update without buffer, 2: no update (exchange only).
-// Grid: x = workgroups of 4 wave tiles (optionally remapped so that each XCD walks one
+// Grid: x = workgroups of FUSED_WAVES wave tiles (optionally remapped so that each XCD walks one
 //       contiguous range), y = chunks of PPB units.  The mask nibble and the packed position
 //       of a lane's four coordinates are computed once and reused for all PPB units of the
 //       chunk.  Waves never talk to each other: no LDS, no barrier.
@@ -434,15 +440,15 @@ __device__ __forceinline__ void finish_unit(const FusedArgs& A, Operands& o, int
 }
 
 template <int MODE, int PPB, bool NT>
-__global__ __launch_bounds__(BLOCK) void fused_round_kernel(MaskParams P, FusedArgs A, Units U) {
+__global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, FusedArgs A, Units U) {
     uint32_t blk = blockIdx.x;
     if (A.xcd_remap) {
         // workgroups are dealt round-robin to the 8 XCDs; give XCD x the range [x*per, (x+1)*per)
-        const uint32_t nblk = (A.ntiles + WAVES - 1) / WAVES;
+        const uint32_t nblk = (A.ntiles + FUSED_WAVES - 1) / FUSED_WAVES;
         const uint32_t per = (nblk + 7u) >> 3;
         blk = (blockIdx.x & 7u) * per + (blockIdx.x >> 3);
     }
-    const uint32_t tile = blk * WAVES + (threadIdx.x >> 6);          // wave-uniform
+    const uint32_t tile = blk * FUSED_WAVES + (threadIdx.x >> 6);    // wave-uniform
     if (tile >= A.ntiles) return;
     const uint32_t q = tile * 64u + (threadIdx.x & 63u);
     const uint32_t j0 = q << 2;
@@ -451,6 +457,7 @@ __global__ __launch_bounds__(BLOCK) void fused_round_kernel(MaskParams P, FusedA
     const int u_lo = blockIdx.y * PPB;
     const int u_hi = min(u_lo + PPB, A.n_units);
     const int64_t K = *A.K_int;
+    if (MODE == 2 && A.tile_cnt[tile] == 0u) return;                  // nothing of this tile is exchanged
 
     // the first unit's operands are requested before the mask arithmetic so that the Philox
     // rounds run while the loads are in flight
@@ -464,7 +471,6 @@ __global__ __launch_bounds__(BLOCK) void fused_round_kernel(MaskParams P, FusedA
     uint32_t total;
     const uint32_t pos0 = tile_base_of(A.grp_base, A.tile_cnt, tile) + wave_prefix(m, total);
     if (K > A.cap) return;                                            // nothing may be written
-    if (MODE == 2 && total == 0u) return;                             // nothing of this tile is exchanged
     if (blockIdx.y == 0 && A.idx && m) {
         uint32_t pos = pos0;
 #pragma unroll
