@@ -97,6 +97,13 @@ saps_status saps_round(saps_ctx* ctx, float* X, const float* G, float* V, float 
                        uint64_t seed, uint64_t round, const int32_t* peer,
                        uint32_t* idx, float* msg, int64_t* K_dev);
 
+/* Consensus diagnostics (Sec. II-C: consensus means that the workers' distance to the average
+ * model goes to zero; Theorem 1 bounds sum_i ||mean - x_i||^2).  Writes the average model
+ * mean_out[j] = (1/n) sum_i X[i][j] (device, N floats, may be NULL) and the total disagreement
+ * *D_dev = sum_i sum_j (X[i][j] - mean[j])^2 (device double, 8-byte aligned), accumulated in fp64
+ * in a fixed order, so repeated calls give identical bits.  X is read once and not modified. */
+saps_status saps_consensus(saps_ctx* ctx, const float* X, float* mean_out, double* D_dev);
+
 /* Waits for the context's stream, returns SAPS_ECAPACITY if any call since the last poll
  * was skipped for K > msg_ld (and clears that flag), else SAPS_OK.  If K_host != NULL it
  * receives the K of the most recent mask generation. */
@@ -117,8 +124,8 @@ enum {
 saps_status saps_set_tuning(saps_ctx* ctx, int32_t knob, int32_t value);
 
 /* Per-kernel timing for benchmarks.  saps_profile_enable(ctx, 1) makes every following
- * saps_round / saps_sgd_step / saps_stream_copy bracket its dominant kernel (the fused
- * round kernel, the list exchange kernel, the update kernel, the copy kernel) with a pair of
+ * saps_round / saps_sgd_step / saps_consensus / saps_stream_copy bracket its dominant kernel (the fused
+ * round kernel, the list exchange kernel, the update kernel, the consensus kernel, the copy kernel) with a pair of
  * HIP events on the context's stream (at most 4096 pairs are kept; later launches are not
  * recorded).  saps_profile_read waits for the stream, returns the number of recorded
  * launches and the sum of their durations in milliseconds, and forgets them. */

@@ -21,6 +21,8 @@
 //            masked coordinates of matched rows become (own + peer)/2, everything else
 //            is unchanged.  Matrix form: Eq. (6) without the gradient term.
 //   round    Alg. 2 order: update, then mask/compact, then merge.
+//   consensus  Sec. II-C: the average model and sum_i ||x_i - mean||^2 (the quantity Theorem 1
+//            bounds), by the two-pass textbook definition in fp64.
 //
 // Pinned by tests/test_oracle_*.py (known-answer vectors, brute force against the
 // explicit matrices M and W, closed forms and invariants).
@@ -30,6 +32,7 @@
 #include <cmath>
 #include <cstdint>
 #include <cstring>
+#include <vector>
 
 namespace {
 
@@ -198,6 +201,29 @@ int oracle_round(int32_t n, int64_t N, int64_t ld, int32_t n_seg, const int64_t*
     rc = oracle_mask_compact(n, N, ld, n_seg, seg_off, seg_c, X, seed, round, idx, msg, msg_ld, K_out);
     if (rc) return rc;
     return oracle_merge(n, N, ld, X, peer, idx, msg, msg_ld, *K_out);
+}
+
+// Sec. II-C / Theorem 1: average model (rounded to fp32) and total disagreement, two passes in fp64.
+int oracle_consensus(int32_t n, int64_t N, int64_t ld, const float* X, float* mean_out, double* D_out) {
+    if (n < 1 || N < 0 || ld < N || !X || !D_out) return ORACLE_EINVAL;
+    std::vector<double> mean(static_cast<size_t>(N), 0.0);
+    for (int32_t i = 0; i < n; ++i)
+        for (int64_t j = 0; j < N; ++j) mean[j] += static_cast<double>(X[i * ld + j]);
+    for (int64_t j = 0; j < N; ++j) {
+        mean[j] /= static_cast<double>(n);
+        if (mean_out) mean_out[j] = static_cast<float>(mean[j]);
+    }
+    double D = 0.0;
+    for (int32_t i = 0; i < n; ++i) {
+        double row = 0.0;
+        for (int64_t j = 0; j < N; ++j) {
+            const double d = static_cast<double>(X[i * ld + j]) - mean[j];
+            row += d * d;
+        }
+        D += row;
+    }
+    *D_out = D;
+    return ORACLE_OK;
 }
 
 }  // extern "C"

@@ -49,6 +49,7 @@ def lib() -> C.CDLL:
         L.oracle_merge.argtypes = [i32, i64, i64, vp, vp, vp, vp, i64, i64]; L.oracle_merge.restype = C.c_int
         L.oracle_round.argtypes = [i32, i64, i64, i32, vp, vp, vp, vp, vp, f32, f32, u64, u64, vp, vp, vp, i64, vp]
         L.oracle_round.restype = C.c_int
+        L.oracle_consensus.argtypes = [i32, i64, i64, vp, vp, vp]; L.oracle_consensus.restype = C.c_int
         _lib = L
     return _lib
 
@@ -141,3 +142,16 @@ def round_(X: np.ndarray, G: Optional[np.ndarray], V: Optional[np.ndarray], N: i
     rc = lib().oracle_round(n, N, ld, len(sc), _p(so), _p(sc), _p(X), _p(G), _p(V), lr, mu, seed, rnd,
                             _p(peer), _p(idx), _p(msg), msg_ld, _p(K))
     return rc, int(K[0]), idx, msg
+
+
+def consensus(X: np.ndarray, N: Optional[int] = None):
+    """Returns (mean fp32[N], D) = average model and sum_i ||x_i - mean||^2."""
+    _chk(X, np.float32, "X")
+    n, ld = X.shape
+    N = ld if N is None else N
+    mean = np.zeros(N, dtype=np.float32)
+    D = np.zeros(1, dtype=np.float64)
+    rc = lib().oracle_consensus(n, N, ld, _p(X), _p(mean), _p(D))
+    if rc:
+        raise ValueError(f"oracle_consensus rc={rc}")
+    return mean, float(D[0])

@@ -21,7 +21,7 @@ _NAMES = {OK: "SAPS_OK", EINVAL: "SAPS_EINVAL", EMATCH: "SAPS_EMATCH", ECAPACITY
 
 EXPORTS = ("saps_abi_version", "saps_create", "saps_destroy", "saps_sgd_step", "saps_mask_compact", "saps_merge",
            "saps_round", "saps_poll_status", "saps_last_error", "saps_set_tuning", "saps_stream_copy",
-           "saps_profile_enable", "saps_profile_read")
+           "saps_profile_enable", "saps_profile_read", "saps_consensus")
 
 
 class SapsError(RuntimeError):
@@ -59,6 +59,7 @@ def load_library() -> C.CDLL:
     L.saps_last_error.argtypes = [vp]; L.saps_last_error.restype = C.c_char_p
     L.saps_set_tuning.argtypes = [vp, i32, i32]; L.saps_set_tuning.restype = C.c_int
     L.saps_stream_copy.argtypes = [vp, vp, vp, i64]; L.saps_stream_copy.restype = C.c_int
+    L.saps_consensus.argtypes = [vp, vp, vp, vp]; L.saps_consensus.restype = C.c_int
     L.saps_profile_enable.argtypes = [vp, i32]; L.saps_profile_enable.restype = C.c_int
     L.saps_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]; L.saps_profile_read.restype = C.c_int
     _lib = L
@@ -184,3 +185,11 @@ class SapsContext:
         cnt = C.c_int32(0); ms = C.c_double(0.0)
         self._rc(self._L.saps_profile_read(self._h, C.byref(cnt), C.byref(ms)), True)
         return int(cnt.value), float(ms.value)
+
+    def saps_consensus(self, X, mean_out, D_dev, check: bool = True) -> int:
+        if mean_out is not None and mean_out.numel() < self.N:
+            raise ValueError("mean_out: fewer than N entries")
+        if D_dev.numel() < 1:
+            raise ValueError("D_dev: empty")
+        return self._rc(self._L.saps_consensus(self._h, self._rows(X, "X"), _dev(mean_out, torch.float32, "mean_out"),
+                                               _dev(D_dev, torch.float64, "D_dev")), check)

@@ -45,6 +45,7 @@ struct saps_ctx {
     uint32_t* d_grp = nullptr;          // ngroups counts, then exclusive bases after the scan
     int64_t* d_K = nullptr;             // K of the most recent mask generation
     int32_t* d_flag = nullptr;          // sticky capacity flag
+    double* d_partial = nullptr;        // one fp64 partial per workgroup of the consensus kernel
     uint32_t* d_idx = nullptr;          // msg_ld entries, used when the caller passes idx == NULL
     int32_t* d_match = nullptr;         // units[2n], only used when the list is too long for the kernel arguments
     Slot ring[RING];
@@ -250,6 +251,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
     chk(hipMalloc(&c->d_tile, sizeof(uint32_t) * ((size_t)c->ntiles + 1)));
     chk(hipMalloc(&c->d_grp, sizeof(uint32_t) * ((size_t)c->ngroups + 1)));
     chk(hipMalloc(&c->d_K, sizeof(int64_t)));
+    chk(hipMalloc(&c->d_partial, sizeof(double) * ((size_t)((L->N + 4 * BLOCK - 1) / (4 * BLOCK)) + 1)));
     chk(hipMalloc(&c->d_flag, sizeof(int32_t)));
     chk(hipMalloc(&c->d_idx, sizeof(uint32_t) * (size_t)std::max<int64_t>(msg_ld, 4)));
     chk(hipMalloc(&c->d_match, sizeof(int32_t) * 2 * (size_t)c->n));
@@ -273,7 +275,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
 saps_status saps_destroy(saps_ctx* c) {
     if (!c) return SAPS_EINVAL;
     (void)hipStreamSynchronize(c->stream);
-    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_tile); (void)hipFree(c->d_grp); (void)hipFree(c->d_K);
+    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_tile); (void)hipFree(c->d_grp); (void)hipFree(c->d_K); (void)hipFree(c->d_partial);
     (void)hipFree(c->d_flag); (void)hipFree(c->d_idx); (void)hipFree(c->d_match);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (int r = 0; r < RING; ++r) {
@@ -406,6 +408,22 @@ saps_status saps_round(saps_ctx* c, float* X, const float* G, float* V, float lr
                            X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);
         profile_mark(c, true);
     }
+    SAPS_HIP(c, hipGetLastError());
+    return SAPS_OK;
+}
+
+saps_status saps_consensus(saps_ctx* c, const float* X, float* mean_out, double* D_dev) {
+    if (!c) return SAPS_EINVAL;
+    if (!X || !D_dev || !aligned16(X) || !aligned16(mean_out) || (reinterpret_cast<uintptr_t>(D_dev) & 7u))
+        return fail(c, SAPS_EINVAL, "X/mean/D null or misaligned");
+    const uint32_t blocks = (uint32_t)((c->N + 4 * BLOCK - 1) / (4 * BLOCK));
+    if (blocks > 0) {
+        profile_mark(c, false);
+        if (c->nontemporal) hipLaunchKernelGGL(consensus_kernel<true>, dim3(blocks), dim3(BLOCK), 0, c->stream, X, c->ld, (uint32_t)c->N, c->n, mean_out, c->d_partial);
+        else hipLaunchKernelGGL(consensus_kernel<false>, dim3(blocks), dim3(BLOCK), 0, c->stream, X, c->ld, (uint32_t)c->N, c->n, mean_out, c->d_partial);
+        profile_mark(c, true);
+    }
+    hipLaunchKernelGGL(consensus_finish_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_partial, blocks, D_dev);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;
 }

@@ -500,6 +500,89 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
     }
 }
 
+// ------------------------------------------------------- K9: consensus diagnostics
+// Mean model and total disagreement  D = sum_i ||x_i - mean||^2  (the quantity whose decay
+// Sec. II-C calls consensus and Theorem 1 bounds).  Lane = one 16-byte column group; it walks
+// the n rows once, keeping sum and sum of squares per coordinate in fp64, so that
+// D_j = sum x^2 - (sum x)^2 / n loses nothing that matters.  Workgroup partials are written
+// out and added by K10 in a fixed order: the result does not depend on scheduling.
+template <bool NT>
+__global__ __launch_bounds__(BLOCK) void consensus_kernel(const float* __restrict__ X, int64_t ld, uint32_t N, int32_t n,
+                                                          float* __restrict__ mean_out, double* __restrict__ partial) {
+    __shared__ double wsum[WAVES];
+    const uint32_t q = blockIdx.x * BLOCK + threadIdx.x;
+    const uint32_t j0 = q << 2;
+    double d = 0.0;
+    if (j0 < N) {
+        const uint32_t nval = min(4u, N - j0);
+        double s[4] = {0.0, 0.0, 0.0, 0.0}, ss[4] = {0.0, 0.0, 0.0, 0.0};
+        const float* col = X + j0;
+        if (nval == 4u) {
+            int32_t i = 0;
+            for (; i + 4 <= n; i += 4) {                 // four rows in flight
+                f4 a[4];
+#pragma unroll
+                for (int k = 0; k < 4; ++k) a[k] = ld4<NT>(col + (int64_t)(i + k) * ld);
+#pragma unroll
+                for (int k = 0; k < 4; ++k)
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) { const double x = (double)a[k][r]; s[r] += x; ss[r] = fma(x, x, ss[r]); }
+            }
+            for (; i < n; ++i) {
+                const f4 a = ld4<NT>(col + (int64_t)i * ld);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) { const double x = (double)a[r]; s[r] += x; ss[r] = fma(x, x, ss[r]); }
+            }
+        } else {
+            for (int32_t i = 0; i < n; ++i)
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+                    if ((uint32_t)r < nval) { const double x = (double)col[(int64_t)i * ld + r]; s[r] += x; ss[r] = fma(x, x, ss[r]); }
+        }
+        const double dn = (double)n;
+        f4 mean = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            if ((uint32_t)r < nval) {
+                const double m = s[r] / dn;
+                mean[r] = (float)m;
+                d += fma(-m, s[r], ss[r]);               // sum x^2 - (sum x)^2 / n
+            }
+        }
+        if (mean_out) {
+            if (nval == 4u) *reinterpret_cast<f4*>(mean_out + j0) = mean;
+            else {
+#pragma unroll
+                for (int r = 0; r < 3; ++r) if ((uint32_t)r < nval) mean_out[j0 + r] = mean[r];
+            }
+        }
+    }
+    // fixed-order workgroup sum: lanes by xor swaps, then the four waves in order
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) d += __shfl_xor(d, o, 64);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = d;
+    __syncthreads();
+    if (threadIdx.x == 0) partial[blockIdx.x] = ((wsum[0] + wsum[1]) + wsum[2]) + wsum[3];
+}
+
+// K10: one workgroup adds the partials in a fixed order.
+__global__ __launch_bounds__(1024) void consensus_finish_kernel(const double* __restrict__ partial, uint32_t count,
+                                                                double* __restrict__ D_out) {
+    __shared__ double wsum[16];
+    double d = 0.0;
+    for (uint32_t k = threadIdx.x; k < count; k += 1024u) d += partial[k];
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) d += __shfl_xor(d, o, 64);
+    if ((threadIdx.x & 63) == 0) wsum[threadIdx.x >> 6] = d;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        double t = 0.0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) t += wsum[w];
+        *D_out = t;
+    }
+}
+
 // --------------------------------------------------------- bandwidth yardstick (a copy)
 template <bool NT>
 __global__ __launch_bounds__(BLOCK) void stream_copy_kernel(float* __restrict__ dst, const float* __restrict__ src,

@@ -283,3 +283,38 @@ def test_expected_traffic_matches_2N_over_c():
     N, c = 272_474, 100.0
     Ks = [int(O.mask(N, 0, t, c).sum()) for t in range(1, 21)]
     assert abs(np.mean(Ks) - N / c) < 5 * np.sqrt(N / c / 20)
+
+
+# ------------------------------------------------------------------ consensus diagnostics
+def test_consensus_matches_numpy_and_closed_forms():
+    rng = np.random.default_rng(21)
+    n, N, ld = 7, 3001, 3008
+    X = np.full((n, ld), 1e9, np.float32)                  # padding must be ignored
+    X[:, :N] = rng.standard_normal((n, N)).astype(np.float32)
+    mean, D = O.consensus(X, N)
+    X64 = X[:, :N].astype(np.float64)
+    assert np.array_equal(mean, X64.mean(0).astype(np.float32))
+    assert abs(D - ((X64 - X64.mean(0)) ** 2).sum()) <= 1e-12 * D
+    # identical rows: zero disagreement
+    Y = np.repeat(X[:1], n, axis=0).copy()
+    assert O.consensus(Y, N)[1] == 0.0
+    # rows a + i*b (exact in fp32): D = sum_j b_j^2 * sum_i (i - (n-1)/2)^2
+    a = rng.integers(-8, 8, N).astype(np.float32); b = rng.integers(-4, 4, N).astype(np.float32)
+    Z = np.stack([a + i * b for i in range(n)]).astype(np.float32)
+    want = float((b.astype(np.float64) ** 2).sum() * sum((i - (n - 1) / 2) ** 2 for i in range(n)))
+    m, D = O.consensus(np.ascontiguousarray(Z))
+    assert D == want and np.array_equal(m, (a + (n - 1) / 2 * b).astype(np.float32))
+
+
+def test_dense_pair_averaging_lowers_disagreement_by_half_the_pair_distances():
+    # For W = (I + P)/2:  D(XW) = D(X) - 1/2 * sum over pairs ||x_i - x_p||^2, and the mean is unchanged.
+    n, N = 6, 4000
+    rng = np.random.default_rng(22)
+    X = rng.integers(-64, 64, (n, N)).astype(np.float32)     # small integers: averaging is exact
+    peer = np.array([1, 0, 4, 5, 2, 3])
+    m0, D0 = O.consensus(X)
+    pair = sum(float(((X[i].astype(np.float64) - X[p]) ** 2).sum()) for i, p in enumerate(peer) if p > i)
+    O.round_(X, None, None, N, 0, 0, 3, 1, peer, 1.0)
+    m1, D1 = O.consensus(X)
+    assert np.array_equal(m0, m1)
+    assert abs(D1 - (D0 - 0.5 * pair)) <= 1e-12 * D0
