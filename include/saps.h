@@ -97,6 +97,16 @@ saps_status saps_round(saps_ctx* ctx, float* X, const float* G, float* V, float 
                        uint64_t seed, uint64_t round, const int32_t* peer,
                        uint32_t* idx, float* msg, int64_t* K_dev);
 
+/* saps_round with options.  flags = 0 is saps_round.  SAPS_ROUND_EQ6_ORDER selects the order of
+ * Eq. (6): X_{t+1} = X_t o notM + (X_t o M) W - gamma G(X_t), i.e. the models of the start of the
+ * round are packed and averaged and the local step computed from G is subtracted afterwards
+ * (bit-identical to saps_mask_compact; saps_merge; saps_sgd_step).  The packed messages then carry
+ * the values before the step.  Without gradients (G == NULL) both orders coincide. */
+enum { SAPS_ROUND_EQ6_ORDER = 1u };
+saps_status saps_round_ex(saps_ctx* ctx, float* X, const float* G, float* V, float lr, float mu,
+                          uint64_t seed, uint64_t round, const int32_t* peer,
+                          uint32_t* idx, float* msg, int64_t* K_dev, uint32_t flags);
+
 /* Consensus diagnostics (Sec. II-C: consensus means that the workers' distance to the average
  * model goes to zero; Theorem 1 bounds sum_i ||mean - x_i||^2).  Writes the average model
  * mean_out[j] = (1/n) sum_i X[i][j] (device, N floats, may be NULL) and the total disagreement

@@ -203,6 +203,23 @@ int oracle_round(int32_t n, int64_t N, int64_t ld, int32_t n_seg, const int64_t*
     return oracle_merge(n, N, ld, X, peer, idx, msg, msg_ld, *K_out);
 }
 
+// One round in the order of Eq. (6): X_{t+1} = X_t o notM + (X_t o M) W - gamma G(X_t).
+// The models of the start of the round are packed and averaged; the local step (with the
+// build's momentum form) is applied afterwards to the mixed models.
+int oracle_round_eq6(int32_t n, int64_t N, int64_t ld, int32_t n_seg, const int64_t* seg_off, const double* seg_c,
+                     float* X, const float* G, float* V, float lr, float mu, uint64_t seed, uint64_t round,
+                     const int32_t* peer, uint32_t* idx, float* msg, int64_t msg_ld, int64_t* K_out) {
+    if (!layout_ok(n, N, ld, n_seg, seg_off, seg_c) || !X || !peer || !idx || !msg || !K_out) return ORACLE_EINVAL;
+    if (!matching_ok(n, peer)) return ORACLE_EMATCH;
+    if (G && !V && mu != 0.0f) return ORACLE_EINVAL;
+    int rc = oracle_mask_compact(n, N, ld, n_seg, seg_off, seg_c, X, seed, round, idx, msg, msg_ld, K_out);
+    if (rc) return rc;                                  // capacity overflow: nothing was written
+    rc = oracle_merge(n, N, ld, X, peer, idx, msg, msg_ld, *K_out);
+    if (rc) return rc;
+    if (G) rc = oracle_sgd_step(n, N, ld, X, G, V, lr, mu);
+    return rc;
+}
+
 // Sec. II-C / Theorem 1: average model (rounded to fp32) and total disagreement, two passes in fp64.
 int oracle_consensus(int32_t n, int64_t N, int64_t ld, const float* X, float* mean_out, double* D_out) {
     if (n < 1 || N < 0 || ld < N || !X || !D_out) return ORACLE_EINVAL;

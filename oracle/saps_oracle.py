@@ -49,6 +49,7 @@ def lib() -> C.CDLL:
         L.oracle_merge.argtypes = [i32, i64, i64, vp, vp, vp, vp, i64, i64]; L.oracle_merge.restype = C.c_int
         L.oracle_round.argtypes = [i32, i64, i64, i32, vp, vp, vp, vp, vp, f32, f32, u64, u64, vp, vp, vp, i64, vp]
         L.oracle_round.restype = C.c_int
+        L.oracle_round_eq6.argtypes = L.oracle_round.argtypes; L.oracle_round_eq6.restype = C.c_int
         L.oracle_consensus.argtypes = [i32, i64, i64, vp, vp, vp]; L.oracle_consensus.restype = C.c_int
         _lib = L
     return _lib
@@ -125,8 +126,9 @@ def merge(X: np.ndarray, N: int, peer: np.ndarray, idx: np.ndarray, msg: np.ndar
 
 
 def round_(X: np.ndarray, G: Optional[np.ndarray], V: Optional[np.ndarray], N: int, lr: float, mu: float,
-           seed: int, rnd: int, peer: np.ndarray, seg_c, seg_off=None, msg_ld: Optional[int] = None):
-    """One round in place on X (and V).  Returns (rc, K, idx, msg)."""
+           seed: int, rnd: int, peer: np.ndarray, seg_c, seg_off=None, msg_ld: Optional[int] = None, eq6: bool = False):
+    """One round in place on X (and V), in Alg. 2 order or (eq6=True) in the order of Eq. (6).
+    Returns (rc, K, idx, msg)."""
     _chk(X, np.float32, "X")
     if G is not None:
         _chk(G, np.float32, "G")
@@ -139,8 +141,9 @@ def round_(X: np.ndarray, G: Optional[np.ndarray], V: Optional[np.ndarray], N: i
     idx = np.zeros(msg_ld, dtype=np.uint32)
     msg = np.zeros((n, msg_ld), dtype=np.float32)
     K = np.zeros(1, dtype=np.int64)
-    rc = lib().oracle_round(n, N, ld, len(sc), _p(so), _p(sc), _p(X), _p(G), _p(V), lr, mu, seed, rnd,
-                            _p(peer), _p(idx), _p(msg), msg_ld, _p(K))
+    fn = lib().oracle_round_eq6 if eq6 else lib().oracle_round
+    rc = fn(n, N, ld, len(sc), _p(so), _p(sc), _p(X), _p(G), _p(V), lr, mu, seed, rnd,
+            _p(peer), _p(idx), _p(msg), msg_ld, _p(K))
     return rc, int(K[0]), idx, msg
 
 

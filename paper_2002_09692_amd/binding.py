@@ -16,12 +16,13 @@ import torch  # loaded first so that libsaps.so binds to the HIP runtime torch a
 from .build import LIB
 
 OK, EINVAL, EMATCH, ECAPACITY, EHIP = 0, 1, 2, 3, 4
+ROUND_EQ6_ORDER = 1
 TUNE_PAIRS_PER_BLOCK, TUNE_XCD_REMAP, TUNE_NONTEMPORAL, TUNE_EXCHANGE_PATH, TUNE_BLOCKS_PER_CU = 0, 1, 2, 3, 4
 _NAMES = {OK: "SAPS_OK", EINVAL: "SAPS_EINVAL", EMATCH: "SAPS_EMATCH", ECAPACITY: "SAPS_ECAPACITY", EHIP: "SAPS_EHIP"}
 
 EXPORTS = ("saps_abi_version", "saps_create", "saps_destroy", "saps_sgd_step", "saps_mask_compact", "saps_merge",
            "saps_round", "saps_poll_status", "saps_last_error", "saps_set_tuning", "saps_stream_copy",
-           "saps_profile_enable", "saps_profile_read", "saps_consensus")
+           "saps_profile_enable", "saps_profile_read", "saps_consensus", "saps_round_ex")
 
 
 class SapsError(RuntimeError):
@@ -59,6 +60,7 @@ def load_library() -> C.CDLL:
     L.saps_last_error.argtypes = [vp]; L.saps_last_error.restype = C.c_char_p
     L.saps_set_tuning.argtypes = [vp, i32, i32]; L.saps_set_tuning.restype = C.c_int
     L.saps_stream_copy.argtypes = [vp, vp, vp, i64]; L.saps_stream_copy.restype = C.c_int
+    L.saps_round_ex.argtypes = [vp, vp, vp, vp, f32, f32, u64, u64, vp, vp, vp, vp, C.c_uint32]; L.saps_round_ex.restype = C.c_int
     L.saps_consensus.argtypes = [vp, vp, vp, vp]; L.saps_consensus.restype = C.c_int
     L.saps_profile_enable.argtypes = [vp, i32]; L.saps_profile_enable.restype = C.c_int
     L.saps_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]; L.saps_profile_read.restype = C.c_int
@@ -193,3 +195,12 @@ class SapsContext:
             raise ValueError("D_dev: empty")
         return self._rc(self._L.saps_consensus(self._h, self._rows(X, "X"), _dev(mean_out, torch.float32, "mean_out"),
                                                _dev(D_dev, torch.float64, "D_dev")), check)
+
+    def saps_round_ex(self, X, G, V, lr: float, mu: float, seed: int, rnd: int, peer, idx=None, msg=None, K_dev=None,
+                      flags: int = 0, check: bool = True) -> int:
+        p = _peer(peer)
+        if p.shape != (self.n,):
+            raise ValueError("peer: need n entries")
+        return self._rc(self._L.saps_round_ex(self._h, self._rows(X, "X"), self._rows(G, "G"), self._rows(V, "V"), lr, mu,
+                                              seed, rnd, p.ctypes.data_as(C.c_void_p), self._idx(idx), self._msg(msg),
+                                              self._K(K_dev), flags), check)

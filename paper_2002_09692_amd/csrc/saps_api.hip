@@ -180,26 +180,33 @@ uint32_t list_grid_x(const saps_ctx* c) {
 }
 
 template <int MODE, int PPB>
-void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, dim3 grid) {
+void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, dim3 grid, bool eq6) {
     const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(c->blocks_per_cu);
-    if (c->nontemporal)
-        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
-    else
-        hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
+    if (MODE != 2 && eq6) {
+        if (c->nontemporal)
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
+        else
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
+    } else {
+        if (c->nontemporal)
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
+        else
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
+    }
 }
 
 template <int MODE>
-void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U) {
+void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U, bool eq6 = false) {
     int ppb = c->ppb;
     const uint32_t nblk = (c->ntiles + FUSED_WAVES - 1) / FUSED_WAVES;
     const uint32_t gx = c->xcd_remap ? 8u * ((nblk + 7u) / 8u) : nblk;
     A.xcd_remap = c->xcd_remap;
     const dim3 grid(gx, (uint32_t)((A.n_units + ppb - 1) / ppb));
     switch (ppb) {
-        case 1: launch_fused_nt<MODE, 1>(c, P, A, U, grid); break;
-        case 2: launch_fused_nt<MODE, 2>(c, P, A, U, grid); break;
-        case 4: launch_fused_nt<MODE, 4>(c, P, A, U, grid); break;
-        default: launch_fused_nt<MODE, 8>(c, P, A, U, grid); break;
+        case 1: launch_fused_nt<MODE, 1>(c, P, A, U, grid, eq6); break;
+        case 2: launch_fused_nt<MODE, 2>(c, P, A, U, grid, eq6); break;
+        case 4: launch_fused_nt<MODE, 4>(c, P, A, U, grid, eq6); break;
+        default: launch_fused_nt<MODE, 8>(c, P, A, U, grid, eq6); break;
     }
 }
 
@@ -368,7 +375,15 @@ saps_status saps_merge(saps_ctx* c, float* X, const int32_t* peer, const uint32_
 saps_status saps_round(saps_ctx* c, float* X, const float* G, float* V, float lr, float mu,
                        uint64_t seed, uint64_t round, const int32_t* peer,
                        uint32_t* idx, float* msg, int64_t* K_dev) {
+    return saps_round_ex(c, X, G, V, lr, mu, seed, round, peer, idx, msg, K_dev, 0u);
+}
+
+saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float lr, float mu,
+                          uint64_t seed, uint64_t round, const int32_t* peer,
+                          uint32_t* idx, float* msg, int64_t* K_dev, uint32_t flags) {
     if (!c) return SAPS_EINVAL;
+    if (flags & ~(uint32_t)SAPS_ROUND_EQ6_ORDER) return fail(c, SAPS_EINVAL, "unknown flag");
+    const bool eq6 = (flags & SAPS_ROUND_EQ6_ORDER) != 0;
     if (!X || !peer) return fail(c, SAPS_EINVAL, "null pointer");
     if (!aligned16(X) || !aligned16(G) || !aligned16(V) || !aligned16(idx) || !aligned16(msg) ||
         (reinterpret_cast<uintptr_t>(K_dev) & 7u))
@@ -394,7 +409,7 @@ saps_status saps_round(saps_ctx* c, float* X, const float* G, float* V, float lr
 
     if (G) {
         profile_mark(c, false);
-        if (V) launch_fused<0>(c, P, A, U); else launch_fused<1>(c, P, A, U);
+        if (V) launch_fused<0>(c, P, A, U, eq6); else launch_fused<1>(c, P, A, U, eq6);
         profile_mark(c, true);
     } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 0.125)) {
         profile_mark(c, false);

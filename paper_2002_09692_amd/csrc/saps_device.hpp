@@ -384,12 +384,14 @@ __device__ __forceinline__ Operands load_unit(const FusedArgs& A, int32_t i, int
 }
 
 // Local step, message write, averaging and write-back of one unit at one lane.
-template <int MODE, bool NT>
+// EQ6 = false: Alg. 2 order (step, then exchange of the stepped values).
+// EQ6 = true:  Eq. (6) order (exchange the values of X_t, then subtract the step computed at X_t).
+template <int MODE, bool NT, bool EQ6>
 __device__ __forceinline__ void finish_unit(const FusedArgs& A, Operands& o, int32_t i, int32_t p, uint32_t j0,
                                             uint32_t nval, uint32_t m, uint32_t pos0) {
     const bool paired = (p != i);
     const int64_t ei = (int64_t)i * A.ld + j0, ep = (int64_t)p * A.ld + j0;
-    if (MODE != 2) {
+    if (MODE != 2 && !EQ6) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             float x = o.xi[r], v = o.vi[r];
@@ -417,6 +419,17 @@ __device__ __forceinline__ void finish_unit(const FusedArgs& A, Operands& o, int
             }
         }
     }
+    if (MODE != 2 && EQ6) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+            float x = o.xi[r], v = o.vi[r];
+            step1<MODE == 0>(x, o.gi[r], v, A.lr, A.mu);
+            o.xi[r] = x; o.vi[r] = v;
+            x = o.xp[r]; v = o.vp[r];
+            step1<MODE == 0>(x, o.gp[r], v, A.lr, A.mu);
+            o.xp[r] = x; o.vp[r] = v;
+        }
+    }
     if (nval == 4u) {
         if (MODE != 2 || paired) st4<NT>(A.X + ei, o.xi);
         if (MODE == 0) st4<NT>(A.V + ei, o.vi);
@@ -439,7 +452,7 @@ __device__ __forceinline__ void finish_unit(const FusedArgs& A, Operands& o, int
     }
 }
 
-template <int MODE, int PPB, bool NT>
+template <int MODE, int PPB, bool NT, bool EQ6>
 __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, FusedArgs A, Units U) {
     uint32_t blk = blockIdx.x;
     if (A.xcd_remap) {
@@ -483,7 +496,7 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
         for (int u = u_lo; u < u_hi; ++u) {
             unit_at(U, u, i, p);
             cur = load_unit<MODE, NT>(A, i, p, j0, nval);
-            finish_unit<MODE, NT>(A, cur, i, p, j0, nval, m, pos0);
+            finish_unit<MODE, NT, EQ6>(A, cur, i, p, j0, nval, m, pos0);
         }
         return;
     }
@@ -495,7 +508,7 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
             unit_at(U, u + 1, in, pn);
             nxt = load_unit<MODE, NT>(A, in, pn, j0, nval);
         }
-        finish_unit<MODE, NT>(A, cur, i, p, j0, nval, m, pos0);
+        finish_unit<MODE, NT, EQ6>(A, cur, i, p, j0, nval, m, pos0);
         if (PPB > 1) { cur = nxt; i = in; p = pn; }
     }
 }

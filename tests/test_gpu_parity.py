@@ -394,3 +394,49 @@ def test_many_workers_unit_list_in_device_memory(B, n):
             ctx.saps_merge(X, peer, idx, msg, Kd)
         assert ctx.saps_poll_status() == (0, K)
     assert_bits(X.cpu().numpy(), Xo, "X")
+
+
+# ------------------------------------------------------------------ Eq. (6) ordering
+@pytest.mark.parametrize("n,N,ld,c", SHAPES)
+@pytest.mark.parametrize("with_v", [True, False])
+def test_eq6_order_round(B, n, N, ld, c, with_v):
+    peer = rand_peer(n, n + 2 * N, singles=1 if n > 2 else 0)
+    msg_ld = (N + 3) // 4 * 4
+    X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2, pad=555.0, scale=1e-3)
+    V0 = rand_models(n, N, ld, 3, pad=333.0, scale=1e-3) if with_v else None
+    mu = 0.9 if with_v else 0.0
+    Xo = X0.copy(); Vo = None if V0 is None else V0.copy()
+    rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.1, mu, 5, 3, peer, c, msg_ld=msg_ld, eq6=True)
+    assert rc == O.OK
+    outs = []
+    for fused in (True, False):
+        X, G = dev(X0), dev(G0); V = None if V0 is None else dev(V0)
+        idx = torch.full((max(msg_ld, 4),), -1, dtype=torch.int32, device="cuda")
+        msg = torch.full((n, msg_ld), -5.0, device="cuda"); Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+        with B.SapsContext(n, N, ld, msg_ld, c) as ctx:
+            if fused:
+                ctx.saps_round_ex(X, G, V, 0.1, mu, 5, 3, peer, idx, msg, Kd, flags=B.ROUND_EQ6_ORDER)
+            else:
+                ctx.saps_mask_compact(X, 5, 3, idx, msg, Kd)
+                ctx.saps_merge(X, peer, idx, msg, Kd)
+                ctx.saps_sgd_step(X, G, V, 0.1, mu)
+            assert ctx.saps_poll_status() == (0, K)
+        assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K])
+        assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], "msg")
+        assert np.all(msg.cpu().numpy()[:, K:] == -5.0)
+        assert_bits(X.cpu().numpy(), Xo, f"X fused={fused}")
+        if with_v:
+            assert_bits(V.cpu().numpy(), Vo, f"V fused={fused}")
+
+
+def test_round_ex_rejects_unknown_flags_and_flag0_is_saps_round(B):
+    n, N, ld = 4, 6000, 6016
+    X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2, scale=1e-3); peer = rand_peer(n, 1)
+    X = dev(X0); G = dev(G0); V = torch.zeros_like(X)
+    with B.SapsContext(n, N, ld, 6000, 8.0) as ctx:
+        assert ctx.saps_round_ex(X, G, V, 0.1, 0.9, 1, 1, peer, flags=2, check=False) == B.EINVAL
+        ctx.saps_round_ex(X, G, V, 0.1, 0.9, 1, 1, peer, flags=0)
+        X2 = dev(X0); V2 = torch.zeros_like(X2)
+        ctx.saps_round(X2, G, V2, 0.1, 0.9, 1, 1, peer)
+        assert ctx.saps_poll_status()[0] == 0
+    assert torch.equal(X.view(torch.int32), X2.view(torch.int32)) and torch.equal(V.view(torch.int32), V2.view(torch.int32))

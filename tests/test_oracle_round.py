@@ -318,3 +318,46 @@ def test_dense_pair_averaging_lowers_disagreement_by_half_the_pair_distances():
     m1, D1 = O.consensus(X)
     assert np.array_equal(m0, m1)
     assert abs(D1 - (D0 - 0.5 * pair)) <= 1e-12 * D0
+
+
+# ------------------------------------------------------------------- Eq. (6) ordering
+@pytest.mark.parametrize("c", [1, 2, 4])
+def test_eq6_order_equals_explicit_matrix_form_with_gradient_term(c):
+    # X_{t+1} = X o notM + (X o M) W - gamma G(X_t), plain SGD (no momentum buffer)
+    n, N = 4, 64
+    rng = np.random.default_rng(31 + c)
+    lr = np.float32(0.125)
+    for rnd, peer in enumerate(_matchings4(), start=1):
+        X = rng.standard_normal((n, N)).astype(np.float32)
+        G = rng.standard_normal((n, N)).astype(np.float32)
+        m = _mask_indep(N, 5, rnd, c)
+        Xp = X.T.astype(np.float64)
+        M = np.repeat(m[:, None], n, axis=1).astype(np.float64)
+        mixed = (Xp * (1 - M) + (Xp * M) @ _W(peer)).T.astype(np.float32)          # exact halves, one rounding
+        want = (mixed.astype(np.float64) - np.float64(lr) * G.astype(np.float64)).astype(np.float32)
+        got = X.copy()
+        rc, K, idx, msg = O.round_(got, G, None, N, float(lr), 0.0, 5, rnd, np.array(peer), float(c), eq6=True)
+        assert rc == O.OK and K == int(m.sum())
+        assert np.array_equal(msg[:, :K], X[:, m])                                  # messages carry X_t
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+
+
+def test_eq6_and_alg2_orders_differ_only_on_masked_coordinates_of_matched_rows():
+    n, N = 4, 2000
+    rng = np.random.default_rng(40)
+    X = rng.standard_normal((n, N)).astype(np.float32); G = rng.standard_normal((n, N)).astype(np.float32)
+    V = rng.standard_normal((n, N)).astype(np.float32)
+    peer = np.array([1, 0, 2, 3])                                                  # rows 2, 3 unmatched
+    A, VA, Bm, VB = X.copy(), V.copy(), X.copy(), V.copy()
+    _, K, idx, _ = O.round_(A, G, VA, N, 0.1, 0.9, 7, 1, peer, 4.0)
+    O.round_(Bm, G, VB, N, 0.1, 0.9, 7, 1, peer, 4.0, eq6=True)
+    m = np.zeros(N, bool); m[idx[:K]] = True
+    assert np.array_equal(VA, VB)                                                   # the buffer never sees the exchange
+    assert np.array_equal(A[:, ~m], Bm[:, ~m]) and np.array_equal(A[2:], Bm[2:])
+    assert not np.array_equal(A[:2, m], Bm[:2, m])
+    # under Eq. (6) the pair keeps a difference of gamma * (v_p - v_i) on masked coordinates; under Alg. 2 none
+    assert np.array_equal(A[0, m], A[1, m]) and not np.array_equal(Bm[0, m], Bm[1, m])
+    # without gradients both orders are the same exchange
+    C1, C2 = X.copy(), X.copy()
+    O.round_(C1, None, None, N, 0, 0, 7, 1, peer, 4.0); O.round_(C2, None, None, N, 0, 0, 7, 1, peer, 4.0, eq6=True)
+    assert np.array_equal(C1, C2)
