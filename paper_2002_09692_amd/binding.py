@@ -83,6 +83,65 @@ def _peer(peer) -> np.ndarray:
     return np.ascontiguousarray(peer, dtype=np.int32)
 
 
+class _SelectInfo(C.Structure):
+    _fields_ = [("rc_connected", C.c_int32), ("rc_components", C.c_int32), ("first_pairs", C.c_int32),
+                ("second_pairs", C.c_int32), ("min_bandwidth", C.c_double), ("mean_bandwidth", C.c_double)]
+
+
+SELECT_EXPORTS = ("saps_selector_create", "saps_selector_destroy", "saps_selector_next", "saps_selector_get_R",
+                  "saps_max_matching")
+
+
+class PeerSelector:
+    """Host-side adaptive peer selection (include/saps_select.h): Alg. 3 round by round."""
+
+    def __init__(self, B: np.ndarray, B_thres: float, T_thres: int, seed: int = 0):
+        L = load_library()
+        L.saps_selector_create.argtypes = [C.POINTER(C.c_void_p), C.c_int32, C.c_void_p, C.c_double, C.c_int64, C.c_uint64]
+        L.saps_selector_next.argtypes = [C.c_void_p, C.c_int64, C.c_void_p, C.POINTER(_SelectInfo)]
+        L.saps_selector_get_R.argtypes = [C.c_void_p, C.c_void_p]
+        L.saps_selector_destroy.argtypes = [C.c_void_p]
+        Bc = np.ascontiguousarray(B, dtype=np.float64)
+        if Bc.ndim != 2 or Bc.shape[0] != Bc.shape[1]:
+            raise ValueError("B: need a square matrix")
+        self.n = Bc.shape[0]
+        h = C.c_void_p()
+        if L.saps_selector_create(C.byref(h), self.n, Bc.ctypes.data_as(C.c_void_p), B_thres, T_thres, seed) != 0:
+            raise SapsError(EINVAL, "saps_selector_create")
+        self._h, self._L = h, L
+
+    def saps_selector_next(self, t: int):
+        """Returns (peer[n] int32, info dict) for round t."""
+        peer = np.empty(self.n, dtype=np.int32)
+        info = _SelectInfo()
+        if self._L.saps_selector_next(self._h, t, peer.ctypes.data_as(C.c_void_p), C.byref(info)) != 0:
+            raise SapsError(EINVAL, "saps_selector_next")
+        return peer, {k: getattr(info, k) for k, _ in _SelectInfo._fields_}
+
+    def saps_selector_get_R(self) -> np.ndarray:
+        R = np.empty((self.n, self.n), dtype=np.int64)
+        self._L.saps_selector_get_R(self._h, R.ctypes.data_as(C.c_void_p))
+        return R
+
+    def close(self):
+        if getattr(self, "_h", None):
+            self._L.saps_selector_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+
+def saps_max_matching(E: np.ndarray, seed: int = 0):
+    """Maximum-cardinality matching of the graph E (n x n 0/1).  Returns (pairs, peer[n])."""
+    L = load_library()
+    L.saps_max_matching.argtypes = [C.c_int32, C.c_void_p, C.c_uint64, C.c_void_p]
+    Ec = np.ascontiguousarray(E, dtype=np.uint8)
+    n = Ec.shape[0]
+    peer = np.empty(n, dtype=np.int32)
+    pairs = L.saps_max_matching(n, Ec.ctypes.data_as(C.c_void_p), seed, peer.ctypes.data_as(C.c_void_p))
+    return int(pairs), peer
+
+
 class SapsContext:
     """saps_create / saps_destroy plus the per-round entry points as methods with the C names."""
 

@@ -5,8 +5,11 @@ import os
 import subprocess
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-SRC = os.path.join(HERE, "csrc", "saps_api.hip")
-DEPS = [SRC, os.path.join(HERE, "csrc", "saps_device.hpp"), os.path.join(os.path.dirname(HERE), "include", "saps.h")]
+SRC = os.path.join(HERE, "csrc", "saps_api.hip")            # HIP kernels + round ABI
+SRC_HOST = os.path.join(HERE, "csrc", "saps_select.cpp")     # host-only peer selection
+DEPS = [SRC, SRC_HOST, os.path.join(HERE, "csrc", "saps_device.hpp"),
+        os.path.join(os.path.dirname(HERE), "include", "saps.h"),
+        os.path.join(os.path.dirname(HERE), "include", "saps_select.h")]
 LIB = os.path.join(HERE, "libsaps.so")
 
 HIPCC_FLAGS = [
@@ -22,7 +25,7 @@ def build(force: bool = True) -> str:
         return LIB
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     tmp = LIB + ".tmp.%d" % os.getpid()
-    subprocess.run([hipcc, *HIPCC_FLAGS, SRC, "-o", tmp], check=True)
+    subprocess.run([hipcc, *HIPCC_FLAGS, SRC, SRC_HOST, "-o", tmp], check=True)
     os.replace(tmp, LIB)
     return LIB
 
