@@ -31,7 +31,7 @@ def main() -> int:
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg3", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5", "mnist_cnn", "cifar10_cnn"])
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg (no cpu_baseline, no parity check)")
     ap.add_argument("--cpu-rounds", type=int, default=None)
     ap.add_argument("--tune", default="", help="comma list knob=value, e.g. ppb=8,xcd=1,nt=1,path=1")
@@ -65,12 +65,13 @@ def main() -> int:
     # X, G, V are carved back to back out of one device arena (a flat parameter arena is the natural
     # home of n replicas); besides fewer allocations this keeps the three streams from starting at
     # the same offset inside a 2 MiB page, which measures 3-5 % faster than three separate tensors
-    arena = torch.empty((3 if wl.fused else 1) * n * ld, dtype=torch.float32, device="cuda")
+    arena = torch.empty((3 if wl.has_buffer else 2 if wl.fused else 1) * n * ld, dtype=torch.float32, device="cuda")
     X = arena[0:n * ld].view(n, ld); X.copy_(torch.from_numpy(X0))
     G = V = None
     if wl.fused:
         G = arena[n * ld:2 * n * ld].view(n, ld); G.copy_(torch.from_numpy(G0))
-        V = arena[2 * n * ld:3 * n * ld].view(n, ld); V.zero_()
+        if wl.has_buffer:
+            V = arena[2 * n * ld:3 * n * ld].view(n, ld); V.zero_()
     idx = torch.zeros(cap, dtype=torch.int32, device="cuda")
     msg = torch.zeros((n, cap), dtype=torch.float32, device="cuda")
     Ks = torch.zeros(warm + steps + 8, dtype=torch.int64, device="cuda")
@@ -88,8 +89,8 @@ def main() -> int:
     parity = "not checked (--no-cpu)"
     if not args.no_cpu:
         from oracle import saps_oracle as O
-        r_cpu = args.cpu_rounds if args.cpu_rounds is not None else {"cfg1": 10, "cfg2": 50, "cfg5": 1}.get(args.workload, 2)
-        Xo = X0.copy(); Vo = np.zeros_like(Xo) if wl.fused else None
+        r_cpu = args.cpu_rounds if args.cpu_rounds is not None else wl.rounds   # the workload's whole trajectory
+        Xo = X0.copy(); Vo = np.zeros_like(Xo) if wl.has_buffer else None
         t_cpu = 0.0
         Kc = []
         for t in range(1, r_cpu + 1):
@@ -161,8 +162,10 @@ def main() -> int:
     # ---- algorithmic bytes of the dominant kernel per launch
     if wl.fused:
         kernel = "fused_round_kernel (update + mask + compaction + averaging)"
-        alg_bytes = 20.0 * n * N + 4.0 * n * K_mean + 4.0 * K_mean
-        bytes_per_unit = "20 B per worker-coordinate (x,g,v read; x,v written) + 4 B per packed value + 4 B per index"
+        per = 20.0 if wl.has_buffer else 12.0
+        alg_bytes = per * n * N + 4.0 * n * K_mean + 4.0 * K_mean
+        bytes_per_unit = ("20 B per worker-coordinate (x,g,v read; x,v written)" if wl.has_buffer else
+                          "12 B per worker-coordinate (x,g read; x written)") + " + 4 B per packed value + 4 B per index"
     else:
         kernel = "exchange kernel (index-list gather/average/scatter or tile walk)"
         alg_bytes = 12.0 * n * K_mean + 4.0 * K_mean

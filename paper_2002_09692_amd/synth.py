@@ -114,6 +114,11 @@ class Workload:
     g_seed: int = 2
 
     @property
+    def has_buffer(self) -> bool:
+        """True when the round keeps a momentum buffer V (mu != 0)."""
+        return self.fused and self.mu != 0.0
+
+    @property
     def seg_off(self) -> np.ndarray:
         return segment_offsets(self.seg_sizes)
 
@@ -170,7 +175,18 @@ def _wl5() -> Workload:
                     matching="bandwidth")
 
 
-WORKLOADS = {"cfg1": _wl1, "cfg2": _wl2, "cfg3": _wl3, "cfg4": _wl4, "cfg5": _wl5}
+def _wl_mnist_cnn() -> Workload:
+    # Table II: MNIST-CNN, 6,653,628 parameters, LR 0.05, plain SGD (the paper has no momentum), 32 workers, c = 100
+    return Workload("mnist_cnn_n32", 32, 6_653_628, [6_653_628], [0.05], [100.0], 20, True, lr=0.05, mu=0.0)
+
+
+def _wl_cifar10_cnn() -> Workload:
+    # Table II: CIFAR10-CNN, 7,025,886 parameters, LR 0.04, plain SGD, 32 workers, c = 100
+    return Workload("cifar10_cnn_n32", 32, 7_025_886, [7_025_886], [0.05], [100.0], 20, True, lr=0.04, mu=0.0)
+
+
+WORKLOADS = {"cfg1": _wl1, "cfg2": _wl2, "cfg3": _wl3, "cfg4": _wl4, "cfg5": _wl5,
+             "mnist_cnn": _wl_mnist_cnn, "cifar10_cnn": _wl_cifar10_cnn}
 
 
 def workload(name: str) -> Workload:

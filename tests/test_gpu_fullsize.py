@@ -35,10 +35,10 @@ def run_workload(B, name, rounds, check_every=1):
     cap = synth.recommended_capacity(wl)
     X0 = synth.make_models(wl, ld, pad_value=123.0)
     G0 = synth.make_grads(wl, 0, ld, pad_value=321.0) if wl.fused else None
-    Xo = X0.copy(); Vo = np.zeros_like(Xo) if wl.fused else None
+    Xo = X0.copy(); Vo = np.zeros_like(Xo) if wl.has_buffer else None
     X = torch.from_numpy(X0).cuda(); del X0
     G = None if G0 is None else torch.from_numpy(G0).cuda()
-    V = torch.zeros_like(X) if wl.fused else None
+    V = torch.zeros_like(X) if wl.has_buffer else None
     idx = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
     msg = torch.full((n, cap), -5.0, device="cuda")
     Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
@@ -81,3 +81,12 @@ def test_cfg4_resnet50_n32_c1000(B):
 
 def test_cfg5_resnet18_n128_mixed_ratios(B):
     run_workload(B, "cfg5", 1)
+
+
+def test_mnist_cnn_size_plain_sgd_rounds(B):
+    # Table II size 6,653,628 with the paper's plain SGD (no momentum buffer)
+    run_workload(B, "mnist_cnn", 2)
+
+
+def test_cifar10_cnn_size_plain_sgd_rounds(B):
+    run_workload(B, "cifar10_cnn", 2)
