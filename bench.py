@@ -60,7 +60,10 @@ def main() -> int:
     X0 = synth.make_models(wl, ld)
     G0 = synth.make_grads(wl, 0, ld) if wl.fused else None
     log(f"[bench] {wl.name}: n={n} N={N} ld={ld} cap={cap} inputs generated in {time.time() - t0:.1f}s")
-    peers = {t: wl.peers(t) for t in range(1, warm + steps + 8)}
+    # bandwidth workloads draw their matchings from the library's own Alg. 3 peer selection
+    selector = (binding.PeerSelector(wl.bandwidth(), wl.B_thres, wl.T_thres, wl.matching_seed)
+                if wl.matching == "bandwidth" else None)
+    peers = {t: wl.peers(t, selector) for t in range(1, max(warm + steps, wl.rounds) + 8)}
 
     # X, G, V are carved back to back out of one device arena (a flat parameter arena is the natural
     # home of n replicas); besides fewer allocations this keeps the three streams from starting at
@@ -74,7 +77,7 @@ def main() -> int:
             V = arena[2 * n * ld:3 * n * ld].view(n, ld); V.zero_()
     idx = torch.zeros(cap, dtype=torch.int32, device="cuda")
     msg = torch.zeros((n, cap), dtype=torch.float32, device="cuda")
-    Ks = torch.zeros(warm + steps + 8, dtype=torch.int64, device="cuda")
+    Ks = torch.zeros(max(warm + steps, wl.rounds) + 8, dtype=torch.int64, device="cuda")
     lr, mu = (wl.lr, wl.mu) if wl.fused else (0.0, 0.0)
 
     ctx = binding.SapsContext(n, N, ld, cap, wl.seg_c, wl.seg_off)
@@ -189,7 +192,8 @@ def main() -> int:
         "config": {"workload": wl.name, "n_workers": n, "N": N, "ld": ld,
                    "c": sorted(set(wl.seg_c)), "segments": len(wl.seg_sizes),
                    "round": "fused update+exchange" if wl.fused else "exchange only",
-                   "lr": lr, "momentum": mu, "matching": wl.matching,
+                   "lr": lr, "momentum": mu,
+                   "matching": "Alg. 3 peer selection (B_thres 50 Mbps, T_thres 10)" if selector else wl.matching,
                    "gradients": "one synthetic draw reused every round" if wl.fused else None,
                    "msg_capacity": cap, "tune": args.tune or "default",
                    "layout": "X|G|V back to back in one device arena, row stride ld"},

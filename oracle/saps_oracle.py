@@ -16,6 +16,8 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "saps_oracle.cpp")
 _LIB = os.path.join(_HERE, "libsaps_oracle.so")
+# tests of the pins themselves point this at a deliberately broken build of the oracle
+_OVERRIDE = os.environ.get("SAPS_ORACLE_LIB")
 
 OK, EINVAL, EMATCH, ECAPACITY = 0, 1, 2, 3
 
@@ -37,7 +39,7 @@ _lib = None
 def lib() -> C.CDLL:
     global _lib
     if _lib is None:
-        L = C.CDLL(build())
+        L = C.CDLL(_OVERRIDE if _OVERRIDE else build())
         vp, i32, i64, u64, f32, f64 = C.c_void_p, C.c_int32, C.c_int64, C.c_uint64, C.c_float, C.c_double
         L.oracle_philox4x32_10.argtypes = [vp, vp, vp]; L.oracle_philox4x32_10.restype = None
         L.oracle_threshold.argtypes = [f64]; L.oracle_threshold.restype = u64

@@ -51,7 +51,7 @@ struct saps_ctx {
     Slot ring[RING];
     uint64_t calls = 0;
     // launch-shape knobs
-    int32_t ppb = 1, xcd_remap = 0, nontemporal = 1, exchange_path = 0, blocks_per_cu = 6;
+    int32_t ppb = 1, xcd_remap = 0, nontemporal = 1, exchange_path = 0, blocks_per_cu = -1;
     // optional event pairs around the dominant kernel of a call
     bool profiling = false;
     std::vector<hipEvent_t> ev_pool;    // 2 events per record, created on demand
@@ -181,7 +181,10 @@ uint32_t list_grid_x(const saps_ctx* c) {
 
 template <int MODE, int PPB>
 void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, dim3 grid, bool eq6) {
-    const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(c->blocks_per_cu);
+    // measured best on the ResNet-18-sized workload: 6 two-wave workgroups per compute unit when
+    // the momentum buffer is streamed too (ten 16-byte streams per lane), no cap otherwise
+    const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : (MODE == 0 ? 6 : 0);
+    const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(bpc);
     if (MODE != 2 && eq6) {
         if (c->nontemporal)
             hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
@@ -306,7 +309,7 @@ saps_status saps_set_tuning(saps_ctx* c, int32_t knob, int32_t value) {
             if (value != 0 && value != 1) return fail(c, SAPS_EINVAL, "nontemporal");
             c->nontemporal = value; return SAPS_OK;
         case SAPS_TUNE_BLOCKS_PER_CU:
-            if (value != 0 && (value < 3 || value > 16)) return fail(c, SAPS_EINVAL, "blocks per CU");
+            if (value != -1 && value != 0 && (value < 3 || value > 16)) return fail(c, SAPS_EINVAL, "blocks per CU");
             c->blocks_per_cu = value; return SAPS_OK;
         case SAPS_TUNE_EXCHANGE_PATH:
             if (value < 0 || value > 2) return fail(c, SAPS_EINVAL, "exchange path");

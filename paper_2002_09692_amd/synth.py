@@ -133,14 +133,27 @@ class Workload:
     def ld(self, align: int = 64) -> int:
         return (self.N + align - 1) // align * align
 
-    def peers(self, rnd: int) -> np.ndarray:
-        """Peer permutation of round `rnd` (1-based), an involution of range(n)."""
+    B_thres: float = 50.0        # Mbps, for matching == "bandwidth"
+    T_thres: int = 10            # rounds, window of recently connected edges (Alg. 3)
+
+    def bandwidth(self) -> np.ndarray:
+        """The workload's symmetric link-speed matrix (matching == "bandwidth")."""
+        return bandwidth_matrix(self.n, self.matching_seed)
+
+    def peers(self, rnd: int, selector=None) -> np.ndarray:
+        """Peer permutation of round `rnd` (1-based), an involution of range(n).
+
+        For bandwidth workloads a `selector` (an object whose saps_selector_next(rnd) returns
+        (peer, info), i.e. the library's Alg. 3 peer selection created on self.bandwidth() with
+        B_thres / T_thres) may be passed; it is stateful, so rounds must then be asked for in
+        order.  Without one, a stateless randomised greedy matcher stands in."""
         if self.matching == "random":
             rng = np.random.default_rng([self.matching_seed, rnd])
             return random_perfect_matching(self.n, rng)
-        B = bandwidth_matrix(self.n, self.matching_seed)
+        if selector is not None:
+            return np.asarray(selector.saps_selector_next(rnd)[0], dtype=np.int32)
         rng = np.random.default_rng([self.matching_seed, 7, rnd])
-        return bandwidth_matching(B, 50.0, rng)
+        return bandwidth_matching(self.bandwidth(), self.B_thres, rng)
 
 
 def _kaiming(fan: Sequence[int]) -> List[float]:

@@ -44,9 +44,11 @@ def run_workload(B, name, rounds, check_every=1):
     Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
     lr, mu = (wl.lr, wl.mu) if wl.fused else (0.0, 0.0)
     Ks = []
+    # bandwidth workloads: matchings from the library's Alg. 3 peer selection (host code)
+    selector = B.PeerSelector(wl.bandwidth(), wl.B_thres, wl.T_thres, wl.matching_seed) if wl.matching == "bandwidth" else None
     with B.SapsContext(n, N, ld, cap, wl.seg_c, wl.seg_off) as ctx:
         for t in range(1, rounds + 1):
-            peer = wl.peers(t)
+            peer = wl.peers(t, selector)
             assert np.array_equal(peer[peer], np.arange(n))
             rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, lr, mu, 0, t, peer, wl.seg_c, wl.seg_off, msg_ld=cap)
             assert rc == O.OK
