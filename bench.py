@@ -162,6 +162,19 @@ def main() -> int:
     Kt = Ks[warm + 1: warm + 1 + steps].cpu().numpy().astype(np.float64)
     K_mean = float(Kt.mean())
 
+    # ---- consensus diagnostics on the final state (outside the timed region)
+    D_dev = torch.zeros(1, dtype=torch.float64, device="cuda")
+    mean_dev = torch.empty(N, dtype=torch.float32, device="cuda")
+    for _ in range(2):
+        ctx.saps_consensus(X, mean_dev, D_dev)
+    ctx.saps_profile_read()
+    for _ in range(10):
+        ctx.saps_consensus(X, mean_dev, D_dev)
+    dl, dms = ctx.saps_profile_read()
+    consensus = {"disagreement_sum_sq": float(D_dev.item()), "kernel_ms": dms / dl,
+                 "algorithmic_GBps": (4.0 * n * N + 4.0 * N) / (dms / dl * 1e-3) / 1e9,
+                 "bytes_per_unit": "4 B per worker-coordinate read + 4 B per coordinate of the mean written"}
+
     # ---- algorithmic bytes of the dominant kernel per launch
     if wl.fused:
         kernel = "fused_round_kernel (update + mask + compaction + averaging)"
@@ -207,6 +220,7 @@ def main() -> int:
         "whole_round_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "event_ms_per_step": ev_ms / steps,
         "K_mean": K_mean,
+        "consensus": consensus,
         "traffic_per_worker_bytes": {"measured_8K": 8.0 * K_mean, "paper_2N_over_c_x4B": 8.0 * wl.expected_K},
         "paper_context": "Table IV, 32 workers, c=100: SAPS-PSGD reaches its target accuracies with 10/120/80 MB of "
                          "traffic per worker (hardware unnamed); the paper reports no timing for this path",

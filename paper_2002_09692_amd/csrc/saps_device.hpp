@@ -19,6 +19,10 @@ constexpr int GROUP = 16;           // tiles per group: the counting kernel's wo
 constexpr int MAX_INLINE_UNITS = 128;
 constexpr int FUSED_BLOCK = 128;    // lanes per workgroup of the fused round kernel (2 independent waves)
 constexpr int FUSED_WAVES = FUSED_BLOCK / 64;
+#ifndef SAPS_CONS_ROWS
+#define SAPS_CONS_ROWS 8
+#endif
+constexpr int CONS_ROWS = SAPS_CONS_ROWS;   // rows a lane of the consensus kernel keeps in flight
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
@@ -532,12 +536,12 @@ __global__ __launch_bounds__(BLOCK) void consensus_kernel(const float* __restric
         const float* col = X + j0;
         if (nval == 4u) {
             int32_t i = 0;
-            for (; i + 4 <= n; i += 4) {                 // four rows in flight
-                f4 a[4];
+            for (; i + CONS_ROWS <= n; i += CONS_ROWS) {   // CONS_ROWS rows in flight
+                f4 a[CONS_ROWS];
 #pragma unroll
-                for (int k = 0; k < 4; ++k) a[k] = ld4<NT>(col + (int64_t)(i + k) * ld);
+                for (int k = 0; k < CONS_ROWS; ++k) a[k] = ld4<NT>(col + (int64_t)(i + k) * ld);
 #pragma unroll
-                for (int k = 0; k < 4; ++k)
+                for (int k = 0; k < CONS_ROWS; ++k)
 #pragma unroll
                     for (int r = 0; r < 4; ++r) { const double x = (double)a[k][r]; s[r] += x; ss[r] = fma(x, x, ss[r]); }
             }
