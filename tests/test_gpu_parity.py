@@ -440,3 +440,58 @@ def test_round_ex_rejects_unknown_flags_and_flag0_is_saps_round(B):
         ctx.saps_round(X2, G, V2, 0.1, 0.9, 1, 1, peer)
         assert ctx.saps_poll_status()[0] == 0
     assert torch.equal(X.view(torch.int32), X2.view(torch.int32)) and torch.equal(V.view(torch.int32), V2.view(torch.int32))
+
+
+# ------------------------------------------------------------------- pipelined calls
+@pytest.mark.parametrize("fused", [True, False])
+def test_many_rounds_enqueued_without_host_synchronisation(B, fused):
+    # 30 rounds back to back with no host synchronisation in between: the context's scratch is reused by
+    # every call, so stream order alone must keep every round's K and the final state exact
+    n, N, ld, c, rounds = 6, 150_003, 150_016, 20.0, 30
+    cap = 9000
+    X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2, scale=1e-3) if fused else None
+    Xo = X0.copy(); Vo = np.zeros_like(Xo) if fused else None
+    peers = [rand_peer(n, 100 + t, singles=t % 2) for t in range(rounds)]
+    Ks_o = []
+    for t in range(rounds):
+        rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.05, 0.9 if fused else 0.0, 77, t + 1, peers[t], c, msg_ld=cap)
+        assert rc == O.OK
+        Ks_o.append(K)
+    X = dev(X0); G = dev(G0) if fused else None; V = torch.zeros_like(X) if fused else None
+    idx = torch.zeros(cap, dtype=torch.int32, device="cuda"); msg = torch.zeros((n, cap), device="cuda")
+    Ks = torch.full((rounds,), -1, dtype=torch.int64, device="cuda")
+    with B.SapsContext(n, N, ld, cap, c) as ctx:
+        for t in range(rounds):
+            ctx.saps_round(X, G, V, 0.05, 0.9 if fused else 0.0, 77, t + 1, peers[t], idx, msg, Ks[t:t + 1])
+        assert ctx.saps_poll_status() == (0, Ks_o[-1])
+    assert Ks.cpu().tolist() == Ks_o
+    K = Ks_o[-1]
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K])
+    assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], "msg")
+    assert_bits(X.cpu().numpy(), Xo, "X")
+    if fused:
+        assert_bits(V.cpu().numpy(), Vo, "V")
+
+
+def test_two_contexts_on_two_streams_do_not_disturb_each_other(B):
+    n, N, ld, c = 4, 80_000, 80_000, 10.0
+    cap = 9000
+    X0 = rand_models(n, N, ld, 5); peer = rand_peer(n, 2)
+    Xo = X0.copy()
+    for t in range(1, 6):
+        O.round_(Xo, None, None, N, 0, 0, 3, t, peer, c, msg_ld=cap)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    outs = []
+    ctxs = []
+    for s in (s1, s2):
+        with torch.cuda.stream(s):
+            X = dev(X0)
+        s.synchronize()
+        ctxs.append((B.SapsContext(n, N, ld, cap, c, stream=s), X))
+    for t in range(1, 6):
+        for ctx, X in ctxs:
+            ctx.saps_round(X, None, None, 0, 0, 3, t, peer)
+    for ctx, X in ctxs:
+        assert ctx.saps_poll_status()[0] == 0
+        assert_bits(X.cpu().numpy(), Xo, "X")
+        ctx.close()
