@@ -92,3 +92,46 @@ def test_mnist_cnn_size_plain_sgd_rounds(B):
 
 def test_cifar10_cnn_size_plain_sgd_rounds(B):
     run_workload(B, "cifar10_cnn", 2)
+
+
+def test_coordinates_above_two_to_the_31(B):
+    # N above 2^31: packed indices, tile numbers and row offsets leave the signed 32-bit range.
+    # Two workers, exchange only, very sparse mask (c = 1e5, about 21,000 kept coordinates).
+    n, N, c = 2, (1 << 31) + 3_000_003, 1.0e5
+    ld = (N + 63) // 64 * 64
+    cap = 24_000
+    X0 = np.empty((n, ld), dtype=np.float32)
+    for i in range(n):
+        base = np.random.default_rng(900 + i).standard_normal(1 << 22, dtype=np.float32)
+        reps = -(-ld // base.size)
+        X0[i] = np.tile(base, reps)[:ld]
+    peer = np.array([1, 0], dtype=np.int32)
+    X = torch.from_numpy(X0).cuda()
+    X_start = X.clone()
+    Xo = X0; del X0                                                       # the oracle works in place
+    rc, K, idx_o, msg_o = O.mask_compact(Xo, N, 12345, 7, c, msg_ld=cap)    # compaction then merge = exchange-only round
+    assert rc == O.OK and abs(K - N / c) < 5 * np.sqrt(N / c)
+    assert O.merge(Xo, N, peer, idx_o, msg_o, K) == O.OK
+    assert int((idx_o[:K] > (1 << 31)).sum()) >= 5                        # the list really reaches the upper half
+    idx = torch.full((cap,), -1, dtype=torch.int32, device="cuda"); msg = torch.full((n, cap), -5.0, device="cuda")
+    Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+    D = torch.zeros(1, dtype=torch.float64, device="cuda")
+    Xo_dev = torch.from_numpy(Xo).cuda()
+    with B.SapsContext(n, N, ld, cap, c) as ctx:
+        ctx.saps_round(X, None, None, 0, 0, 12345, 7, peer, idx, msg, Kd)
+        assert ctx.saps_poll_status() == (0, K)
+        assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K])
+        assert same_bits(msg[:, :K].contiguous(), np.ascontiguousarray(msg_o[:, :K]))
+        assert torch.equal(X.view(torch.int32), Xo_dev.view(torch.int32))
+        # the un-fused entries at the same size, same seed and round, from the same start
+        X.copy_(X_start); idx.fill_(-1); msg.fill_(-5.0)
+        ctx.saps_mask_compact(X, 12345, 7, idx, msg, Kd)
+        ctx.saps_merge(X, peer, idx, msg, Kd)
+        ctx.saps_consensus(X, None, D)
+        assert ctx.saps_poll_status() == (0, K)
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K])
+    assert same_bits(msg[:, :K].contiguous(), np.ascontiguousarray(msg_o[:, :K]))
+    assert torch.equal(X.view(torch.int32), Xo_dev.view(torch.int32))
+    # n = 2: D = ||x0 - x1||^2 / 2, summed here on the device in fp64 from the oracle's result
+    half = 0.5 * float(((Xo_dev[0, :N].double() - Xo_dev[1, :N].double()) ** 2).sum().item())
+    assert abs(float(D.item()) - half) <= 1e-9 * half
