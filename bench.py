@@ -189,11 +189,15 @@ def main() -> int:
     k_ms = kms / max(kl, 1)
     achieved = alg_bytes / (k_ms * 1e-3) / 1e9
 
-    traffic = None
+    # measured HBM bytes per launch of the dominant kernel (rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
+    # same command, scaled by the copy kernel of known size; summaries under profiles/)
+    traffic = traffic_detail = None
     tf = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(tf):
         with open(tf) as f:
-            traffic = json.load(f).get(args.workload)
+            traffic_detail = json.load(f).get(args.workload)
+        if traffic_detail:
+            traffic = traffic_detail["total_bytes"]
 
     out = {
         "metric": "model coords/s per SAPS round",
@@ -211,7 +215,7 @@ def main() -> int:
                    "msg_capacity": cap, "tune": args.tune or "default",
                    "layout": "X|G|V back to back in one device arena, row stride ld"},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic,
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_detail": traffic_detail,
                      "kernel": kernel, "kernel_ms": k_ms, "kernel_launches": kl,
                      "algorithmic_bytes_per_launch": alg_bytes, "bytes_per_unit": bytes_per_unit,
                      "copy_yardstick_GBps": copy_gbps, "frac_of_copy": achieved / copy_gbps},

@@ -39,6 +39,7 @@ struct saps_ctx {
     double density = 0.0;               // expected K / N
     uint32_t* d_seg_end = nullptr;
     uint64_t* d_seg_T = nullptr;
+    uint32_t* d_grp_seg = nullptr;      // first segment intersecting each group of 16 tiles
     // scratch
     uint32_t ngroups = 0;
     uint32_t* d_tile = nullptr;         // ntiles kept counts, one per wave tile
@@ -90,6 +91,7 @@ MaskParams mask_params(const saps_ctx* c, uint64_t seed, uint64_t round) {
     P.T0 = c->T0;
     P.seg_end = c->d_seg_end;
     P.seg_T = c->d_seg_T;
+    P.grp_seg = c->d_grp_seg;
     return P;
 }
 
@@ -258,6 +260,18 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
     auto chk = [&](hipError_t r) { if (e == hipSuccess && r != hipSuccess) e = r; };
     chk(hipMalloc(&c->d_seg_end, sizeof(uint32_t) * seg_end.size()));
     chk(hipMalloc(&c->d_seg_T, sizeof(uint64_t) * seg_T.size()));
+    // first segment that reaches into each group of GROUP tiles (GROUP * TILE coordinates)
+    std::vector<uint32_t> grp_seg((size_t)c->ngroups + 1, 0u);
+    {
+        uint32_t sidx = 0;
+        for (uint32_t g = 0; g < c->ngroups; ++g) {
+            const uint64_t start = (uint64_t)g * GROUP * TILE;
+            while (sidx + 1 < seg_end.size() && (uint64_t)seg_end[sidx] <= start) ++sidx;
+            grp_seg[g] = sidx;
+        }
+    }
+    chk(hipMalloc(&c->d_grp_seg, sizeof(uint32_t) * grp_seg.size()));
+    if (e == hipSuccess) chk(hipMemcpy(c->d_grp_seg, grp_seg.data(), sizeof(uint32_t) * grp_seg.size(), hipMemcpyHostToDevice));
     chk(hipMalloc(&c->d_tile, sizeof(uint32_t) * ((size_t)c->ntiles + 1)));
     chk(hipMalloc(&c->d_grp, sizeof(uint32_t) * ((size_t)c->ngroups + 1)));
     chk(hipMalloc(&c->d_K, sizeof(int64_t)));
@@ -285,7 +299,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
 saps_status saps_destroy(saps_ctx* c) {
     if (!c) return SAPS_EINVAL;
     (void)hipStreamSynchronize(c->stream);
-    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_tile); (void)hipFree(c->d_grp); (void)hipFree(c->d_K); (void)hipFree(c->d_partial);
+    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_grp_seg); (void)hipFree(c->d_tile); (void)hipFree(c->d_grp); (void)hipFree(c->d_K); (void)hipFree(c->d_partial);
     (void)hipFree(c->d_flag); (void)hipFree(c->d_idx); (void)hipFree(c->d_match);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (int r = 0; r < RING; ++r) {

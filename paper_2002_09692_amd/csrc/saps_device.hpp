@@ -35,6 +35,7 @@ struct MaskParams {
     uint64_t T0;              // floor(2^32 / c) of the only segment when n_seg == 1
     const uint32_t* seg_end;  // device: exclusive end of each segment, seg_end[n_seg-1] == N
     const uint64_t* seg_T;    // device: threshold of each segment
+    const uint32_t* grp_seg;  // device: first segment that intersects each group of 16 tiles
 };
 
 // Philox4x32-10 (Salmon et al., SC'11): ten rounds, each two 32x32->64 products, a word
@@ -57,32 +58,36 @@ __device__ __forceinline__ void philox4x32_10(uint32_t& c0, uint32_t& c1, uint32
     }
 }
 
-// First segment that intersects [start, ...): wave-uniform binary search (start is uniform).
-__device__ __forceinline__ int first_segment(const MaskParams& P, uint32_t start) {
-    int lo = 0, hi = P.n_seg - 1;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if (P.seg_end[mid] > start) hi = mid; else lo = mid + 1;
-    }
-    return lo;
+// First segment that intersects tile `tile` (wave-uniform): start from the group's entry of the
+// host-built table and step over the segments that end before the tile begins.
+__device__ __forceinline__ int first_segment(const MaskParams& P, uint32_t tile) {
+    int s = (int)P.grp_seg[tile / GROUP];
+    const uint32_t start = tile * (uint32_t)TILE;
+    const int last = P.n_seg - 1;
+    while (s < last && P.seg_end[s] <= start) ++s;
+    return s;
 }
 
-// Mask nibble of Philox block q (coordinates 4q..4q+3): bit r set iff coordinate 4q+r < N is kept.
-// seg0 = first_segment(tile start), only read when there are several thresholds.
-__device__ __forceinline__ uint32_t mask4(const MaskParams& P, uint32_t q, int seg0) {
+// Mask nibble of lane `lane` of tile `tile` (coordinates 4q..4q+3, q = 64*tile + lane): bit r set
+// iff coordinate 4q+r < N is kept.  seg0 = first_segment(tile), only read when there are
+// several thresholds.
+__device__ __forceinline__ uint32_t mask4(const MaskParams& P, uint32_t tile, uint32_t lane, int seg0) {
+    const uint32_t q = tile * 64u + lane;
     const uint32_t j0 = q << 2;
     if (j0 >= P.N) return 0u;
     uint32_t u0 = q, u1 = 0u, u2 = P.rnd0, u3 = P.rnd1;
     philox4x32_10(u0, u1, u2, u3, P.key0, P.key1);
     uint32_t m;
-    if (P.n_seg == 1) {
-        const uint64_t T = P.T0;
+    const int last = P.n_seg - 1;
+    if (P.n_seg == 1 || seg0 == last || P.seg_end[seg0] - tile * (uint32_t)TILE >= (uint32_t)TILE) {
+        // one threshold for the whole tile (always, when the model has a single ratio)
+        const uint64_t T = (P.n_seg == 1) ? P.T0 : P.seg_T[seg0];
         m = (uint32_t)((uint64_t)u0 < T) | ((uint32_t)((uint64_t)u1 < T) << 1) |
             ((uint32_t)((uint64_t)u2 < T) << 2) | ((uint32_t)((uint64_t)u3 < T) << 3);
     } else {
+        // a segment boundary falls inside the tile: look the threshold up per coordinate
         const uint32_t u[4] = {u0, u1, u2, u3};
         int s = seg0;
-        const int last = P.n_seg - 1;
         m = 0u;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
@@ -137,8 +142,8 @@ __global__ __launch_bounds__(64 * GROUP) void mask_count_kernel(MaskParams P, ui
     const uint32_t tile = blockIdx.x * GROUP + wave;
     uint32_t total = 0u;
     if (tile < ntiles) {
-        const int seg0 = (P.n_seg > 1) ? first_segment(P, tile * (uint32_t)TILE) : 0;
-        const uint32_t m = mask4(P, tile * 64u + (threadIdx.x & 63u), seg0);
+        const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
+        const uint32_t m = mask4(P, tile, threadIdx.x & 63u, seg0);
         (void)wave_prefix(m, total);
         if ((threadIdx.x & 63u) == 0u) tile_cnt[tile] = total;
     }
@@ -218,9 +223,9 @@ __global__ __launch_bounds__(BLOCK) void idx_scatter_kernel(MaskParams P, uint32
     const uint32_t tile = blockIdx.x * WAVES + (threadIdx.x >> 6);
     if (tile >= ntiles) return;
     if (tile_cnt[tile] == 0u) return;                    // nothing kept here: no need to redo the Philox block
-    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile * (uint32_t)TILE) : 0;
+    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
     const uint32_t q = tile * 64u + (threadIdx.x & 63u);
-    const uint32_t m = mask4(P, q, seg0);
+    const uint32_t m = mask4(P, tile, threadIdx.x & 63u, seg0);
     uint32_t total;
     uint32_t pos = tile_base_of(grp_base, tile_cnt, tile) + wave_prefix(m, total);
     if (m) {
@@ -483,8 +488,8 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
     Operands cur;
     if (MODE != 2 && live) cur = load_unit<MODE, NT>(A, i, p, j0, nval);
 
-    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile * (uint32_t)TILE) : 0;
-    const uint32_t m = mask4(P, q, seg0);
+    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
+    const uint32_t m = mask4(P, tile, threadIdx.x & 63u, seg0);
     uint32_t total;
     const uint32_t pos0 = tile_base_of(A.grp_base, A.tile_cnt, tile) + wave_prefix(m, total);
     if (K > A.cap) return;                                            // nothing may be written
