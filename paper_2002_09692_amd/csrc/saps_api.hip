@@ -428,7 +428,9 @@ saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float
         profile_mark(c, false);
         if (V) launch_fused<0>(c, P, A, U, eq6); else launch_fused<1>(c, P, A, U, eq6);
         profile_mark(c, true);
-    } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 0.125)) {
+    } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 1.0 / 12.0 && c->density < 0.2)) {
+        // measured on 32 x 11.2 M: the walk wins around c = 8 (0.62 vs 0.72 ms); for denser masks its
+        // per-lane message stores cost more than the list's coalesced ones (c = 2, 4: 0.82-0.86 vs 0.73 ms)
         profile_mark(c, false);
         launch_fused<2>(c, P, A, U);                   // dense masks: walk the tiles
         profile_mark(c, true);
