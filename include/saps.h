@@ -30,6 +30,8 @@
  *   - K (number of kept coordinates of the round) is known only on the device.  If K exceeds
  *     the capacity msg_ld the round's kernels write NOTHING to X, V, msg, idx (K_dev is
  *     still written) and a sticky flag is raised that saps_poll_status() reports.
+ *   - A context belongs to the device that was current in saps_create(); calling an entry point
+ *     with another device current returns SAPS_EINVAL.
  *   - Host-detectable errors are returned immediately and nothing is enqueued.
  *   - X, G, V, msg, idx must not alias.
  *   - Limits: 1 <= n <= 65535, 0 <= N <= 0xFFFF0000, n_seg >= 1.

@@ -32,6 +32,7 @@ struct saps_ctx {
     int32_t n = 0;
     int64_t N = 0, ld = 0, msg_ld = 0;
     hipStream_t stream = nullptr;
+    int device = 0;                     // the device that was current at creation; all scratch lives there
     uint32_t ntiles = 0;
     // mask description (segments with equal thresholds merged, empty ones dropped)
     int32_t n_seg = 1;
@@ -79,6 +80,14 @@ saps_status hip_fail(saps_ctx* c, hipError_t e, const char* where) {
         hipError_t e__ = (call);                                   \
         if (e__ != hipSuccess) return hip_fail((ctx), e__, #call); \
     } while (0)
+
+// Every entry point must be called with the context's device current (its scratch and stream are there).
+saps_status check_device(saps_ctx* c) {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev != c->device)
+        return fail(c, SAPS_EINVAL, "the context was created on another device than the current one");
+    return SAPS_OK;
+}
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -250,6 +259,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
     if (!c) return SAPS_EINVAL;
     c->n = L->n; c->N = L->N; c->ld = L->ld; c->msg_ld = msg_ld;
     c->stream = (hipStream_t)hip_stream;
+    if (hipGetDevice(&c->device) != hipSuccess) { delete c; return SAPS_EHIP; }
     c->ntiles = (uint32_t)((L->N + TILE - 1) / TILE);
     c->ngroups = (c->ntiles + GROUP - 1) / GROUP;
     c->n_seg = (int32_t)seg_T.size();
@@ -334,6 +344,7 @@ saps_status saps_set_tuning(saps_ctx* c, int32_t knob, int32_t value) {
 
 saps_status saps_sgd_step(saps_ctx* c, float* X, const float* G, float* V, float lr, float mu) {
     if (!c) return SAPS_EINVAL;
+    if (saps_status ds = check_device(c)) return ds;
     if (!X || !G || !aligned16(X) || !aligned16(G) || !aligned16(V)) return fail(c, SAPS_EINVAL, "X/G/V null or misaligned");
     if (!V && mu != 0.0f) return fail(c, SAPS_EINVAL, "momentum needs V");
     if (c->N == 0) return SAPS_OK;
@@ -357,6 +368,7 @@ saps_status saps_sgd_step(saps_ctx* c, float* X, const float* G, float* V, float
 saps_status saps_mask_compact(saps_ctx* c, const float* X, uint64_t seed, uint64_t round,
                               uint32_t* idx, float* msg, int64_t* K_dev) {
     if (!c) return SAPS_EINVAL;
+    if (saps_status ds = check_device(c)) return ds;
     if (!X || !idx || !msg || !K_dev) return fail(c, SAPS_EINVAL, "null pointer");
     if (!aligned16(X) || !aligned16(idx) || !aligned16(msg) || (reinterpret_cast<uintptr_t>(K_dev) & 7u))
         return fail(c, SAPS_EINVAL, "misaligned pointer");
@@ -374,6 +386,7 @@ saps_status saps_mask_compact(saps_ctx* c, const float* X, uint64_t seed, uint64
 saps_status saps_merge(saps_ctx* c, float* X, const int32_t* peer, const uint32_t* idx, const float* msg,
                        const int64_t* K_dev) {
     if (!c) return SAPS_EINVAL;
+    if (saps_status ds = check_device(c)) return ds;
     if (!X || !peer || !idx || !msg || !K_dev) return fail(c, SAPS_EINVAL, "null pointer");
     if (!aligned16(X) || !aligned16(idx) || !aligned16(msg) || (reinterpret_cast<uintptr_t>(K_dev) & 7u))
         return fail(c, SAPS_EINVAL, "misaligned pointer");
@@ -399,6 +412,7 @@ saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float
                           uint64_t seed, uint64_t round, const int32_t* peer,
                           uint32_t* idx, float* msg, int64_t* K_dev, uint32_t flags) {
     if (!c) return SAPS_EINVAL;
+    if (saps_status ds = check_device(c)) return ds;
     if (flags & ~(uint32_t)SAPS_ROUND_EQ6_ORDER) return fail(c, SAPS_EINVAL, "unknown flag");
     const bool eq6 = (flags & SAPS_ROUND_EQ6_ORDER) != 0;
     if (!X || !peer) return fail(c, SAPS_EINVAL, "null pointer");
@@ -448,6 +462,7 @@ saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float
 
 saps_status saps_consensus(saps_ctx* c, const float* X, float* mean_out, double* D_dev) {
     if (!c) return SAPS_EINVAL;
+    if (saps_status ds = check_device(c)) return ds;
     if (!X || !D_dev || !aligned16(X) || !aligned16(mean_out) || (reinterpret_cast<uintptr_t>(D_dev) & 7u))
         return fail(c, SAPS_EINVAL, "X/mean/D null or misaligned");
     const uint32_t blocks = (uint32_t)((c->N + 4 * BLOCK - 1) / (4 * BLOCK));
@@ -498,6 +513,7 @@ saps_status saps_profile_read(saps_ctx* c, int32_t* launches, double* total_ms) 
 
 saps_status saps_stream_copy(saps_ctx* c, float* dst, const float* src, int64_t count) {
     if (!c) return SAPS_EINVAL;
+    if (saps_status ds = check_device(c)) return ds;
     if (!dst || !src || count < 0 || (count & 3) || !aligned16(dst) || !aligned16(src)) return fail(c, SAPS_EINVAL, "copy arguments");
     if (count == 0) return SAPS_OK;
     const int64_t c4 = count / 4;

@@ -495,3 +495,54 @@ def test_two_contexts_on_two_streams_do_not_disturb_each_other(B):
         assert ctx.saps_poll_status()[0] == 0
         assert_bits(X.cpu().numpy(), Xo, "X")
         ctx.close()
+
+
+# --------------------------------------------------------------- seeded random sweep
+def _random_case(rng):
+    n = int(rng.integers(1, 12))
+    N = int(rng.choice([rng.integers(1, 300), rng.integers(300, 6000), rng.integers(6000, 60_000)]))
+    ld = (N + 3) // 4 * 4 + 4 * int(rng.integers(0, 20))
+    nseg = int(rng.choice([1, 1, 2, 5, 40]))
+    cuts = np.sort(rng.integers(0, N + 1, size=nseg - 1)) if nseg > 1 else np.array([], dtype=np.int64)
+    off = np.concatenate([[0], cuts, [N]]).astype(np.int64)
+    cs = rng.choice([1.0, 1.5, 2.0, 3.0, 10.0, 100.0, 1000.0, 1e9], size=nseg).tolist()
+    peer = synth.random_perfect_matching(n, rng)
+    for i in rng.permutation(n)[: int(rng.integers(0, 3))]:
+        p = peer[i]; peer[i], peer[p] = i, p
+    kind = str(rng.choice(["fused", "fused_nov", "eq6", "exchange_list", "exchange_walk"]))
+    return n, N, ld, off, cs, peer, kind, int(rng.integers(0, 2**63)), int(rng.integers(0, 2**63))
+
+
+@pytest.mark.parametrize("case", range(60))
+def test_random_configurations(B, case):
+    rng = np.random.default_rng(5000 + case)
+    n, N, ld, off, cs, peer, kind, seed, rnd = _random_case(rng)
+    msg_ld = (N + 3) // 4 * 4
+    X0 = rand_models(n, N, ld, case)
+    fused = kind in ("fused", "fused_nov", "eq6")
+    G0 = rand_models(n, N, ld, case + 1, pad=1.5, scale=1e-2) if fused else None
+    V0 = rand_models(n, N, ld, case + 2, pad=2.5, scale=1e-2) if kind in ("fused", "eq6") else None
+    mu = 0.9 if V0 is not None else 0.0
+    Xo = X0.copy(); Vo = None if V0 is None else V0.copy()
+    rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.1, mu, seed, rnd, peer, cs, off, msg_ld=msg_ld, eq6=(kind == "eq6"))
+    assert rc == O.OK
+    X = dev(X0); G = None if G0 is None else dev(G0); V = None if V0 is None else dev(V0)
+    idx = torch.full((max(msg_ld, 4),), -1, dtype=torch.int32, device="cuda")
+    msg = torch.full((n, msg_ld), -5.0, device="cuda"); Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+    with B.SapsContext(n, N, ld, msg_ld, cs, off) as ctx:
+        if kind == "exchange_list":
+            ctx.saps_set_tuning(B.TUNE_EXCHANGE_PATH, 1)
+        if kind == "exchange_walk":
+            ctx.saps_set_tuning(B.TUNE_EXCHANGE_PATH, 2)
+            ctx.saps_set_tuning(B.TUNE_PAIRS_PER_BLOCK, int(rng.choice([1, 2, 4, 8])))
+        if fused:
+            ctx.saps_set_tuning(B.TUNE_PAIRS_PER_BLOCK, int(rng.choice([1, 2, 4, 8])))
+        ctx.saps_round_ex(X, G, V, 0.1, mu, seed, rnd, peer, idx, msg, Kd, flags=B.ROUND_EQ6_ORDER if kind == "eq6" else 0)
+        assert ctx.saps_poll_status() == (0, K), (kind, n, N)
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K]), kind
+    assert np.all(idx.cpu().numpy()[K:] == -1)
+    assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], f"msg {kind}")
+    assert np.all(msg.cpu().numpy()[:, K:] == -5.0)
+    assert_bits(X.cpu().numpy(), Xo, f"X {kind} n={n} N={N} ld={ld}")
+    if V is not None:
+        assert_bits(V.cpu().numpy(), Vo, f"V {kind}")
