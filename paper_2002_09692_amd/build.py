@@ -32,3 +32,17 @@ def build(force: bool = True) -> str:
 
 if __name__ == "__main__":
     print(build())
+
+
+NATIVE_TEST_SRC = os.path.join(os.path.dirname(HERE), "tests", "native", "abi_smoke.cpp")
+NATIVE_TEST_BIN = os.path.join(os.path.dirname(HERE), "tests", "native", "abi_smoke.bin")
+
+
+def build_native_test() -> str:
+    """Compiles the stand-alone C++ user of the ABI (tests/native/abi_smoke.cpp) against the in-tree library."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    tmp = NATIVE_TEST_BIN + ".tmp.%d" % os.getpid()
+    subprocess.run([hipcc, "-O2", "--offload-arch=gfx950", "-std=c++17", NATIVE_TEST_SRC, "-L" + HERE, "-lsaps",
+                    "-Wl,-rpath,$ORIGIN/../../paper_2002_09692_amd", "-o", tmp], check=True)
+    os.replace(tmp, NATIVE_TEST_BIN)
+    return NATIVE_TEST_BIN

@@ -546,3 +546,14 @@ def test_random_configurations(B, case):
     assert_bits(X.cpu().numpy(), Xo, f"X {kind} n={n} N={N} ld={ld}")
     if V is not None:
         assert_bits(V.cpu().numpy(), Vo, f"V {kind}")
+
+
+def test_maximum_number_of_workers(B):
+    # n = 65535 (the limit): 32767 pairs and one unmatched worker, unit list in device memory
+    n, N, ld = 65535, 37, 40
+    peer = rand_peer(n, 9)
+    for fused in (True, False):
+        r = run_round_both(B, n, N, ld, 2.0, None, 3, 3, peer, fused=fused)
+        check_round(r, N)
+    with pytest.raises(B.SapsError):
+        B.SapsContext(65536, N, ld, 40, 2.0)
