@@ -189,6 +189,16 @@ def main() -> int:
     k_ms = kms / max(kl, 1)
     achieved = alg_bytes / (k_ms * 1e-3) / 1e9
 
+    # exchange-only rounds touch isolated values, but HBM moves whole lines: bytes of the 128-byte lines
+    # read and 32-byte sectors written that hold the last round's kept coordinates, for comparison
+    line_bytes = None
+    if not wl.fused:
+        K_last = int(Ks[warm + steps].item())
+        j = idx[:K_last].to(torch.int64) & 0xFFFFFFFF
+        lines = int(torch.unique(j >> 5).numel()); sectors = int(torch.unique(j >> 3).numel())
+        line_bytes = {"lines_128B_read_per_row": lines, "sectors_32B_written_per_row": sectors,
+                      "bytes_per_launch": float(n) * (128.0 * lines + 32.0 * sectors) + 4.0 * n * K_last + 4.0 * K_last}
+
     # measured HBM bytes per launch of the dominant kernel (rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this
     # same command, scaled by the copy kernel of known size; summaries under profiles/)
     traffic = traffic_detail = None
@@ -218,7 +228,8 @@ def main() -> int:
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": traffic, "traffic_detail": traffic_detail,
                      "kernel": kernel, "kernel_ms": k_ms, "kernel_launches": kl,
                      "algorithmic_bytes_per_launch": alg_bytes, "bytes_per_unit": bytes_per_unit,
-                     "copy_yardstick_GBps": copy_gbps, "frac_of_copy": achieved / copy_gbps},
+                     "copy_yardstick_GBps": copy_gbps, "frac_of_copy": achieved / copy_gbps,
+                     "line_granular": line_bytes},
         "cpu_baseline": cpu,
         "parity": parity,
         "whole_round_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
