@@ -572,7 +572,7 @@ __global__ __launch_bounds__(BLOCK) void consensus_kernel(const float* __restric
             }
         }
         if (mean_out) {
-            if (nval == 4u) *reinterpret_cast<f4*>(mean_out + j0) = mean;
+            if (nval == 4u) st4<NT>(mean_out + j0, mean);
             else {
 #pragma unroll
                 for (int r = 0; r < 3; ++r) if ((uint32_t)r < nval) mean_out[j0 + r] = mean[r];
