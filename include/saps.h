@@ -95,7 +95,8 @@ saps_status saps_merge(saps_ctx* ctx, float* X, const int32_t* peer, const uint3
  *   saps_sgd_step; saps_mask_compact; saps_merge
  * but with every element of X, G, V read once and X, V written once.  G == NULL skips the
  * local step (exchange-only round; V, lr, mu ignored).  idx, msg, K_dev may each be NULL
- * when the caller does not need that output. */
+ * when the caller does not need that output; the capacity rule (K > msg_ld skips the round)
+ * holds all the same, so msg_ld must cover K even then. */
 saps_status saps_round(saps_ctx* ctx, float* X, const float* G, float* V, float lr, float mu,
                        uint64_t seed, uint64_t round, const int32_t* peer,
                        uint32_t* idx, float* msg, int64_t* K_dev);

@@ -228,7 +228,7 @@ void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U
 
 extern "C" {
 
-int32_t saps_abi_version(void) { return 1; }
+int32_t saps_abi_version(void) { return 2; }
 
 const char* saps_last_error(const saps_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
 
