@@ -173,12 +173,20 @@ void profile_mark(saps_ctx* c, bool second) {
     }
 }
 
-// K1 + K2: per-tile counts, exclusive tile bases, K and the capacity flag.
-saps_status enqueue_count_scan(saps_ctx* c, const MaskParams& P, int64_t* K_user) {
+// Small models skip the scan launch: the kernels that need packed positions add up the (at most
+// 256) group counts themselves.
+bool direct_bases(const saps_ctx* c) { return c->ngroups > 0 && c->ngroups <= DIRECT_MAX_GROUPS; }
+
+// K1 (+ K2 unless the model is small): per-tile and per-group counts, exclusive group bases, K and
+// the capacity flag.  Returns what the position-consuming kernels need.
+saps_status enqueue_count_scan(saps_ctx* c, const MaskParams& P, int64_t* K_user, Bases* Bp) {
+    Bp->grp = c->d_grp; Bp->tile_cnt = c->d_tile; Bp->K_int = c->d_K; Bp->K_user = K_user; Bp->flag = c->d_flag;
+    Bp->cap = c->msg_ld; Bp->ngroups = c->ngroups; Bp->direct = direct_bases(c) ? 1 : 0;
     if (c->ngroups > 0)
         hipLaunchKernelGGL(mask_count_kernel, dim3(c->ngroups), dim3(64 * GROUP), 0, c->stream, P, c->ntiles, c->d_tile, c->d_grp);
-    hipLaunchKernelGGL(group_scan_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_grp, c->ngroups, c->msg_ld,
-                       c->d_K, K_user, c->d_flag);
+    if (!Bp->direct)
+        hipLaunchKernelGGL(group_scan_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_grp, c->ngroups, c->msg_ld,
+                           c->d_K, K_user, c->d_flag);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;
 }
@@ -373,10 +381,11 @@ saps_status saps_mask_compact(saps_ctx* c, const float* X, uint64_t seed, uint64
     if (!aligned16(X) || !aligned16(idx) || !aligned16(msg) || (reinterpret_cast<uintptr_t>(K_dev) & 7u))
         return fail(c, SAPS_EINVAL, "misaligned pointer");
     const MaskParams P = mask_params(c, seed, round);
-    saps_status s = enqueue_count_scan(c, P, K_dev);
+    Bases Bp;
+    saps_status s = enqueue_count_scan(c, P, K_dev, &Bp);
     if (s) return s;
     if (c->ntiles == 0) return SAPS_OK;
-    hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, c->d_grp, c->d_tile, c->d_K, c->msg_ld, idx);
+    hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, Bp, idx);
     hipLaunchKernelGGL(compact_values_kernel, dim3(list_grid_x(c), (uint32_t)c->n), dim3(BLOCK), 0, c->stream,
                        X, c->ld, idx, c->d_K, c->msg_ld, msg, c->msg_ld);
     SAPS_HIP(c, hipGetLastError());
@@ -426,7 +435,8 @@ saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float
     saps_status s = make_units(c, peer, &U, &n_units);
     if (s) return s;
     const MaskParams P = mask_params(c, seed, round);
-    s = enqueue_count_scan(c, P, K_dev);
+    Bases Bp;
+    s = enqueue_count_scan(c, P, K_dev, &Bp);
     if (s) return s;
     if (c->ntiles == 0) return SAPS_OK;
 
@@ -434,7 +444,7 @@ saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float
     A.X = X; A.G = G; A.V = V; A.ld = c->ld;
     A.n_units = n_units;
     A.lr = lr; A.mu = mu;
-    A.grp_base = c->d_grp; A.tile_cnt = c->d_tile; A.K_int = c->d_K; A.cap = c->msg_ld;
+    A.bases = Bp;
     A.idx = idx; A.msg = msg; A.msg_ld = c->msg_ld;
     A.ntiles = c->ntiles; A.xcd_remap = 0;
 
@@ -450,7 +460,7 @@ saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float
         profile_mark(c, true);
     } else {
         uint32_t* list = idx ? idx : c->d_idx;        // sparse masks: go through the index list
-        hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, c->d_grp, c->d_tile, c->d_K, c->msg_ld, list);
+        hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, Bp, list);
         profile_mark(c, false);
         hipLaunchKernelGGL(exchange_list_kernel, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
                            X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);

@@ -202,32 +202,71 @@ __global__ __launch_bounds__(1024) void group_scan_kernel(uint32_t* __restrict__
     }
 }
 
-// Packed position of the first kept coordinate of a tile: its group's base plus the counts of
-// the tiles in front of it inside the group (at most 15 words, one per lane, summed by swaps).
-__device__ __forceinline__ uint32_t tile_base_of(const uint32_t* __restrict__ grp_base,
-                                                 const uint32_t* __restrict__ tile_cnt, uint32_t tile) {
+// Where the packed positions and K of the round come from.
+//   direct == 0: K2 ran; grp holds exclusive group bases and *K_int the total.
+//   direct == 1: small models (at most 256 groups): no K2 launch; grp still holds the group
+//                counts and every wave adds up the ones in front of its group itself; the first
+//                wave of the grid also publishes K and raises the capacity flag.
+struct Bases {
+    const uint32_t* grp;
+    const uint32_t* tile_cnt;
+    int64_t* K_int;
+    int64_t* K_user;      // caller's copy of K, written in direct mode only (K2 writes it otherwise)
+    int32_t* flag;
+    int64_t cap;
+    uint32_t ngroups;
+    int32_t direct;
+};
+constexpr uint32_t DIRECT_MAX_GROUPS = 256;
+
+// Packed position of the first kept coordinate of a tile (its group's base plus the counts of
+// the tiles in front of it inside the group, at most 15 words, one per lane, summed by swaps)
+// and the round's K.  Wave-uniform; every lane of the wave must call it.
+__device__ __forceinline__ uint32_t tile_base_and_K(const Bases& Bp, uint32_t tile, bool first_wave, int64_t& K) {
     const uint32_t g = tile / GROUP, r = tile % GROUP, lane = threadIdx.x & 63u;
-    uint32_t v = (lane < r) ? tile_cnt[g * GROUP + lane] : 0u;
+    uint32_t v = (lane < r) ? Bp.tile_cnt[g * GROUP + lane] : 0u;
+    uint32_t before = 0u, all = 0u;
+    if (Bp.direct) {
+#pragma unroll
+        for (uint32_t k = 0; k < DIRECT_MAX_GROUPS / 64u; ++k) {
+            const uint32_t gi = lane + 64u * k;
+            const uint32_t c = (gi < Bp.ngroups) ? Bp.grp[gi] : 0u;
+            all += c;
+            before += (gi < g) ? c : 0u;
+        }
+    }
 #pragma unroll
     for (int d = 1; d < GROUP; d <<= 1) v += __shfl_xor(v, d, 64);
-    return grp_base[g] + __builtin_amdgcn_readfirstlane(v);
+    if (Bp.direct) {
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) { before += __shfl_xor(before, d, 64); all += __shfl_xor(all, d, 64); }
+        K = (int64_t)all;
+        if (first_wave && lane == 0u) {
+            *Bp.K_int = K;
+            if (Bp.K_user) *Bp.K_user = K;
+            if (K > Bp.cap) *Bp.flag = 1;
+        }
+        return __builtin_amdgcn_readfirstlane(before) + __builtin_amdgcn_readfirstlane(v);
+    }
+    K = *Bp.K_int;
+    return Bp.grp[g] + __builtin_amdgcn_readfirstlane(v);
 }
 
 // --------------------------------------------------------- K3: ascending index list idx
-__global__ __launch_bounds__(BLOCK) void idx_scatter_kernel(MaskParams P, uint32_t ntiles,
-                                                            const uint32_t* __restrict__ grp_base,
-                                                            const uint32_t* __restrict__ tile_cnt,
-                                                            const int64_t* __restrict__ K_int, int64_t cap,
+__global__ __launch_bounds__(BLOCK) void idx_scatter_kernel(MaskParams P, uint32_t ntiles, Bases Bp,
                                                             uint32_t* __restrict__ idx) {
-    if (*K_int > cap) return;
     const uint32_t tile = blockIdx.x * WAVES + (threadIdx.x >> 6);
     if (tile >= ntiles) return;
-    if (tile_cnt[tile] == 0u) return;                    // nothing kept here: no need to redo the Philox block
+    const bool first_wave = (tile == 0u);
+    if (!first_wave && Bp.tile_cnt[tile] == 0u) return;  // nothing kept here: no need to redo the Philox block
+    int64_t K;
+    const uint32_t base = tile_base_and_K(Bp, tile, first_wave, K);
+    if (K > Bp.cap) return;
     const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
     const uint32_t q = tile * 64u + (threadIdx.x & 63u);
     const uint32_t m = mask4(P, tile, threadIdx.x & 63u, seg0);
     uint32_t total;
-    uint32_t pos = tile_base_of(grp_base, tile_cnt, tile) + wave_prefix(m, total);
+    uint32_t pos = base + wave_prefix(m, total);
     if (m) {
 #pragma unroll
         for (int r = 0; r < 4; ++r)
@@ -351,7 +390,7 @@ struct FusedArgs {
     int64_t ld;
     int32_t n_units;
     float lr, mu;
-    const uint32_t* grp_base; const uint32_t* tile_cnt; const int64_t* K_int; int64_t cap;
+    Bases bases;
     uint32_t* idx; float* msg; int64_t msg_ld;
     uint32_t ntiles; int32_t xcd_remap;
 };
@@ -478,8 +517,8 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
     const uint32_t nval = live ? min(4u, P.N - j0) : 0u;
     const int u_lo = blockIdx.y * PPB;
     const int u_hi = min(u_lo + PPB, A.n_units);
-    const int64_t K = *A.K_int;
-    if (MODE == 2 && A.tile_cnt[tile] == 0u) return;                  // nothing of this tile is exchanged
+    const bool first_wave = (tile == 0u && blockIdx.y == 0);
+    if (MODE == 2 && !first_wave && A.bases.tile_cnt[tile] == 0u) return;   // nothing of this tile is exchanged
 
     // the first unit's operands are requested before the mask arithmetic so that the Philox
     // rounds run while the loads are in flight
@@ -491,8 +530,9 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
     const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
     const uint32_t m = mask4(P, tile, threadIdx.x & 63u, seg0);
     uint32_t total;
-    const uint32_t pos0 = tile_base_of(A.grp_base, A.tile_cnt, tile) + wave_prefix(m, total);
-    if (K > A.cap) return;                                            // nothing may be written
+    int64_t K;
+    const uint32_t pos0 = tile_base_and_K(A.bases, tile, first_wave, K) + wave_prefix(m, total);
+    if (K > A.bases.cap) return;                                      // nothing may be written
     if (blockIdx.y == 0 && A.idx && m) {
         uint32_t pos = pos0;
 #pragma unroll
