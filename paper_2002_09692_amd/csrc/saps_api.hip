@@ -2,6 +2,7 @@
 // of a context, and the launch sequences of the SAPS-PSGD round (Alg. 2 lines 5-10).
 #include "saps_device.hpp"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
