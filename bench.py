@@ -48,6 +48,10 @@ def main() -> int:
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
     binding.load_library()
+    # everything runs on one ordinary (non-null) stream: launches on the null stream measured several
+    # microseconds slower each, which matters for the launch-bound small workloads
+    stream = torch.cuda.Stream()
+    torch.cuda.set_stream(stream)
 
     wl = synth.workload(args.workload)
     steps = args.steps if args.steps is not None else wl.rounds
@@ -162,6 +166,27 @@ def main() -> int:
     Kt = Ks[warm + 1: warm + 1 + steps].cpu().numpy().astype(np.float64)
     K_mean = float(Kt.mean())
 
+    # ---- the same `steps` rounds captured once into a HIP graph and replayed (secondary figure; possible
+    # because a round is nothing but kernel launches when the matching fits the kernel arguments)
+    graph_ms_per_step = None
+    if n <= 128:
+        ctx.saps_profile_enable(False)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        t_g = warm
+        with torch.cuda.graph(g, stream=stream):
+            for _ in range(steps):
+                t_g += 1
+                ctx.saps_round(X, G, V, lr, mu, seed, t_g, peers[t_g], idx, msg, Ks[t_g:t_g + 1])
+        g.replay()
+        torch.cuda.synchronize()
+        w0 = time.perf_counter()
+        g.replay()
+        torch.cuda.synchronize()
+        graph_ms_per_step = (time.perf_counter() - w0) * 1e3 / steps
+        assert ctx.saps_poll_status()[0] == 0
+        ctx.saps_profile_enable(True)
+
     # ---- consensus diagnostics on the final state (outside the timed region)
     D_dev = torch.zeros(1, dtype=torch.float64, device="cuda")
     mean_dev = torch.empty(N, dtype=torch.float32, device="cuda")
@@ -240,6 +265,7 @@ def main() -> int:
         "parity": parity,
         "whole_round_GBps": alg_bytes / (ms_per_step * 1e-3) / 1e9,
         "event_ms_per_step": ev_ms / steps,
+        "graph_replay_ms_per_step": graph_ms_per_step,
         "K_mean": K_mean,
         "consensus": consensus,
         "traffic_per_worker_bytes": {"measured_8K": 8.0 * K_mean, "paper_2N_over_c_x4B": 8.0 * wl.expected_K},

@@ -557,3 +557,55 @@ def test_maximum_number_of_workers(B):
         check_round(r, N)
     with pytest.raises(B.SapsError):
         B.SapsContext(65536, N, ld, 40, 2.0)
+
+
+# ------------------------------------------------------------------ HIP graph capture
+@pytest.mark.parametrize("fused", [True, False])
+def test_round_loop_captured_in_a_graph_replays_like_eager(B, fused):
+    # a round is only kernel launches when the matching fits the kernel arguments, so a loop of rounds can
+    # be captured once and replayed; every replay must reproduce the eager result bit for bit
+    n, N, ld, c, T = 8, 120_001, 120_064, 50.0, 6
+    cap = 4000
+    X0h = rand_models(n, N, ld, 1); G0h = rand_models(n, N, ld, 2, scale=1e-3)
+    peers = [rand_peer(n, 40 + t) for t in range(T)]
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        X0 = dev(X0h); G = dev(G0h) if fused else None
+        X = X0.clone(); V = torch.zeros_like(X) if fused else None
+        idx = torch.zeros(cap, dtype=torch.int32, device="cuda"); msg = torch.zeros((n, cap), device="cuda")
+        Ks = torch.zeros(T, dtype=torch.int64, device="cuda")
+    s.synchronize()
+    mu = 0.9 if fused else 0.0
+    with B.SapsContext(n, N, ld, cap, c, stream=s) as ctx:
+        def rounds():
+            for t in range(T):
+                ctx.saps_round(X, G, V, 0.1, mu, 9, t + 1, peers[t], idx, msg, Ks[t:t + 1])
+        rounds()                                                   # eager
+        assert ctx.saps_poll_status()[0] == 0
+        ref = [a.clone() for a in (X, idx, msg, Ks)] + ([V.clone()] if fused else [])
+        # against the oracle too
+        Xo = X0h.copy(); Vo = np.zeros_like(Xo) if fused else None
+        for t in range(T):
+            O.round_(Xo, G0h if fused else None, Vo, N, 0.1, mu, 9, t + 1, peers[t], c, msg_ld=cap)
+        assert_bits(X.cpu().numpy(), Xo, "eager X")
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.stream(s):
+            X.copy_(X0)
+            if fused:
+                V.zero_()
+        s.synchronize()
+        with torch.cuda.graph(g, stream=s):
+            rounds()
+        for rep in range(4):
+            with torch.cuda.stream(s):
+                X.copy_(X0); idx.zero_(); msg.zero_(); Ks.zero_()    # eager work between the replays
+                if fused:
+                    V.zero_()
+            s.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            got = [X, idx, msg, Ks] + ([V] if fused else [])
+            for a, b in zip(got, ref):
+                assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+                                   b.view(torch.int32) if b.dtype == torch.float32 else b), f"replay {rep}"
+        assert ctx.saps_poll_status()[0] == 0
