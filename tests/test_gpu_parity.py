@@ -609,3 +609,41 @@ def test_round_loop_captured_in_a_graph_replays_like_eager(B, fused):
                 assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
                                    b.view(torch.int32) if b.dtype == torch.float32 else b), f"replay {rep}"
         assert ctx.saps_poll_status()[0] == 0
+
+
+# ------------------------------------------------------------- optional outputs, lifetime
+@pytest.mark.parametrize("fused", [True, False])
+@pytest.mark.parametrize("want", ["idx", "msg", "K"])
+def test_each_optional_output_alone(B, fused, want):
+    n, N, ld, c = 4, 45_001, 45_056, 30.0
+    cap = 2000
+    X0 = rand_models(n, N, ld, 3); G0 = rand_models(n, N, ld, 4, scale=1e-3) if fused else None
+    peer = rand_peer(n, 8)
+    Xo = X0.copy(); Vo = np.zeros_like(Xo) if fused else None
+    rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.1, 0.9 if fused else 0.0, 4, 4, peer, c, msg_ld=cap)
+    X = dev(X0); G = dev(G0) if fused else None; V = torch.zeros_like(X) if fused else None
+    idx = torch.full((cap,), -1, dtype=torch.int32, device="cuda") if want == "idx" else None
+    msg = torch.full((n, cap), -5.0, device="cuda") if want == "msg" else None
+    Kd = torch.full((1,), -1, dtype=torch.int64, device="cuda") if want == "K" else None
+    with B.SapsContext(n, N, ld, cap, c) as ctx:
+        ctx.saps_round(X, G, V, 0.1, 0.9 if fused else 0.0, 4, 4, peer, idx, msg, Kd)
+        assert ctx.saps_poll_status() == (0, K)
+    assert_bits(X.cpu().numpy(), Xo, "X")
+    if want == "idx":
+        assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K]) and np.all(idx.cpu().numpy()[K:] == -1)
+    if want == "msg":
+        assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], "msg")
+    if want == "K":
+        assert int(Kd.item()) == K
+
+
+def test_many_contexts_created_and_destroyed(B):
+    X = dev(rand_models(2, 5000, 5056, 1))
+    free0 = torch.cuda.mem_get_info()[0]
+    for k in range(300):
+        with B.SapsContext(2, 5000, 5056, 5000, 4.0) as ctx:
+            if k % 50 == 0:
+                ctx.saps_round(X, None, None, 0, 0, 1, k + 1, np.array([1, 0]))
+                assert ctx.saps_poll_status()[0] == 0
+    torch.cuda.synchronize()
+    assert free0 - torch.cuda.mem_get_info()[0] < (64 << 20)          # contexts give their scratch back
