@@ -279,9 +279,20 @@ template <bool NT> __device__ __forceinline__ f4 ld4(const float* p) {
     if (NT) return __builtin_nontemporal_load(reinterpret_cast<const f4*>(p));
     return *reinterpret_cast<const f4*>(p);
 }
+// Streaming 16-byte store.  The non-temporal flavour carries "sc1 nt" (device-coherent streaming
+// write), which measured 2 % faster than "nt" alone on a plain copy (6.60 vs 6.46 TB/s); the compiler
+// has no builtin for that pair, so the instruction is written out.  The trailing s_nop keeps the
+// required distance to a following overwrite of the data registers, which the compiler cannot see.
 template <bool NT> __device__ __forceinline__ void st4(float* p, f4 v) {
-    if (NT) __builtin_nontemporal_store(v, reinterpret_cast<f4*>(p));
-    else *reinterpret_cast<f4*>(p) = v;
+    if (NT) {
+#ifdef SAPS_PLAIN_NT_STORE
+        __builtin_nontemporal_store(v, reinterpret_cast<f4*>(p));
+#else
+        asm volatile("global_store_dwordx4 %0, %1, off sc1 nt\n\ts_nop 2" : : "v"(p), "v"(v) : "memory");
+#endif
+    } else {
+        *reinterpret_cast<f4*>(p) = v;
+    }
 }
 
 // Local step on one value (Alg. 2 line 5 with momentum): two correctly rounded FMAs.
