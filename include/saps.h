@@ -12,7 +12,7 @@
  *   sparsify        Eq. (2): x~ = x o m; only the non-zeros travel (packed, ascending j)
  *   exchange+merge  Alg. 2 lines 8-10 with GenerateW's weights (1/2, 1/2): masked
  *                   coordinates of two matched workers become the mean of the two,
- *                   all other coordinates keep their value (Eq. (6))
+ *                   all other coordinates keep their value (Eq. (7))
  *
  * The mask is never stored.  Coordinate j of round t is kept iff
  *     Philox4x32-10(key = (lo32 seed, hi32 seed),
@@ -102,12 +102,12 @@ saps_status saps_round(saps_ctx* ctx, float* X, const float* G, float* V, float 
                        uint64_t seed, uint64_t round, const int32_t* peer,
                        uint32_t* idx, float* msg, int64_t* K_dev);
 
-/* saps_round with options.  flags = 0 is saps_round.  SAPS_ROUND_EQ6_ORDER selects the order of
- * Eq. (6): X_{t+1} = X_t o notM + (X_t o M) W - gamma G(X_t), i.e. the models of the start of the
+/* saps_round with options.  flags = 0 is saps_round.  SAPS_ROUND_MIX_THEN_STEP selects the order of
+ * Eq. (7): X_{t+1} = X_t o notM + (X_t o M) W - gamma G(X_t), i.e. the models of the start of the
  * round are packed and averaged and the local step computed from G is subtracted afterwards
  * (bit-identical to saps_mask_compact; saps_merge; saps_sgd_step).  The packed messages then carry
  * the values before the step.  Without gradients (G == NULL) both orders coincide. */
-enum { SAPS_ROUND_EQ6_ORDER = 1u };
+enum { SAPS_ROUND_MIX_THEN_STEP = 1u };
 saps_status saps_round_ex(saps_ctx* ctx, float* X, const float* G, float* V, float lr, float mu,
                           uint64_t seed, uint64_t round, const int32_t* peer,
                           uint32_t* idx, float* msg, int64_t* K_dev, uint32_t flags);

@@ -19,7 +19,7 @@
 //   merge    Alg. 2 lines 8-10 read with the prose of Sec. II-A (the worker averages
 //            what it received with its own values) and GenerateW (weights 1/2, 1/2):
 //            masked coordinates of matched rows become (own + peer)/2, everything else
-//            is unchanged.  Matrix form: Eq. (6) without the gradient term.
+//            is unchanged.  Matrix form: Eq. (7) without the gradient term.
 //   round    Alg. 2 order: update, then mask/compact, then merge.
 //   consensus  Sec. II-C: the average model and sum_i ||x_i - mean||^2 (the quantity Theorem 1
 //            bounds), by the two-pass textbook definition in fp64.
@@ -203,10 +203,10 @@ int oracle_round(int32_t n, int64_t N, int64_t ld, int32_t n_seg, const int64_t*
     return oracle_merge(n, N, ld, X, peer, idx, msg, msg_ld, *K_out);
 }
 
-// One round in the order of Eq. (6): X_{t+1} = X_t o notM + (X_t o M) W - gamma G(X_t).
+// One round in the order of Eq. (7): X_{t+1} = X_t o notM + (X_t o M) W - gamma G(X_t).
 // The models of the start of the round are packed and averaged; the local step (with the
 // build's momentum form) is applied afterwards to the mixed models.
-int oracle_round_eq6(int32_t n, int64_t N, int64_t ld, int32_t n_seg, const int64_t* seg_off, const double* seg_c,
+int oracle_round_mix_then_step(int32_t n, int64_t N, int64_t ld, int32_t n_seg, const int64_t* seg_off, const double* seg_c,
                      float* X, const float* G, float* V, float lr, float mu, uint64_t seed, uint64_t round,
                      const int32_t* peer, uint32_t* idx, float* msg, int64_t msg_ld, int64_t* K_out) {
     if (!layout_ok(n, N, ld, n_seg, seg_off, seg_c) || !X || !peer || !idx || !msg || !K_out) return ORACLE_EINVAL;

@@ -16,8 +16,13 @@ import numpy as np
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "saps_oracle.cpp")
 _LIB = os.path.join(_HERE, "libsaps_oracle.so")
-# tests of the pins themselves point this at a deliberately broken build of the oracle
+# The test of the pins themselves points this at a deliberately broken build of the oracle.  A stray
+# variable must never swap the checker under the other tests, so the override is refused unless that
+# test's own marker variable is set as well.
 _OVERRIDE = os.environ.get("SAPS_ORACLE_LIB")
+if _OVERRIDE and os.environ.get("SAPS_ORACLE_MUTATION_RUN") != "1":
+    raise RuntimeError("SAPS_ORACLE_LIB is set but SAPS_ORACLE_MUTATION_RUN != 1: refusing to replace the oracle "
+                       "(only tests/test_oracle_pins_catch_mistakes.py may do that)")
 
 OK, EINVAL, EMATCH, ECAPACITY = 0, 1, 2, 3
 
@@ -51,7 +56,7 @@ def lib() -> C.CDLL:
         L.oracle_merge.argtypes = [i32, i64, i64, vp, vp, vp, vp, i64, i64]; L.oracle_merge.restype = C.c_int
         L.oracle_round.argtypes = [i32, i64, i64, i32, vp, vp, vp, vp, vp, f32, f32, u64, u64, vp, vp, vp, i64, vp]
         L.oracle_round.restype = C.c_int
-        L.oracle_round_eq6.argtypes = L.oracle_round.argtypes; L.oracle_round_eq6.restype = C.c_int
+        L.oracle_round_mix_then_step.argtypes = L.oracle_round.argtypes; L.oracle_round_mix_then_step.restype = C.c_int
         L.oracle_consensus.argtypes = [i32, i64, i64, vp, vp, vp]; L.oracle_consensus.restype = C.c_int
         _lib = L
     return _lib
@@ -128,8 +133,9 @@ def merge(X: np.ndarray, N: int, peer: np.ndarray, idx: np.ndarray, msg: np.ndar
 
 
 def round_(X: np.ndarray, G: Optional[np.ndarray], V: Optional[np.ndarray], N: int, lr: float, mu: float,
-           seed: int, rnd: int, peer: np.ndarray, seg_c, seg_off=None, msg_ld: Optional[int] = None, eq6: bool = False):
-    """One round in place on X (and V), in Alg. 2 order or (eq6=True) in the order of Eq. (6).
+           seed: int, rnd: int, peer: np.ndarray, seg_c, seg_off=None, msg_ld: Optional[int] = None, mix_first: bool = False):
+    """One round in place on X (and V), in Alg. 2 order or (mix_first=True) in the order of the
+    recursion of Sec. III, Eq. (7): exchange the models of the start of the round, then step.
     Returns (rc, K, idx, msg)."""
     _chk(X, np.float32, "X")
     if G is not None:
@@ -143,7 +149,7 @@ def round_(X: np.ndarray, G: Optional[np.ndarray], V: Optional[np.ndarray], N: i
     idx = np.zeros(msg_ld, dtype=np.uint32)
     msg = np.zeros((n, msg_ld), dtype=np.float32)
     K = np.zeros(1, dtype=np.int64)
-    fn = lib().oracle_round_eq6 if eq6 else lib().oracle_round
+    fn = lib().oracle_round_mix_then_step if mix_first else lib().oracle_round
     rc = fn(n, N, ld, len(sc), _p(so), _p(sc), _p(X), _p(G), _p(V), lr, mu, seed, rnd,
             _p(peer), _p(idx), _p(msg), msg_ld, _p(K))
     return rc, int(K[0]), idx, msg

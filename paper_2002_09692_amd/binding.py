@@ -16,7 +16,7 @@ import torch  # loaded first so that libsaps.so binds to the HIP runtime torch a
 from .build import LIB
 
 OK, EINVAL, EMATCH, ECAPACITY, EHIP = 0, 1, 2, 3, 4
-ROUND_EQ6_ORDER = 1
+ROUND_MIX_THEN_STEP = 1
 TUNE_PAIRS_PER_BLOCK, TUNE_XCD_REMAP, TUNE_NONTEMPORAL, TUNE_EXCHANGE_PATH, TUNE_BLOCKS_PER_CU = 0, 1, 2, 3, 4
 _NAMES = {OK: "SAPS_OK", EINVAL: "SAPS_EINVAL", EMATCH: "SAPS_EMATCH", ECAPACITY: "SAPS_ECAPACITY", EHIP: "SAPS_EHIP"}
 

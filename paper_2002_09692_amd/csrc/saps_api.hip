@@ -200,12 +200,12 @@ uint32_t list_grid_x(const saps_ctx* c) {
 }
 
 template <int MODE, int PPB>
-void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, dim3 grid, bool eq6) {
+void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, dim3 grid, bool mix_first) {
     // measured best on the ResNet-18-sized workload: 6 two-wave workgroups per compute unit when
     // the momentum buffer is streamed too (ten 16-byte streams per lane), no cap otherwise
     const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : (MODE == 0 ? 6 : 0);
     const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(bpc);
-    if (MODE != 2 && eq6) {
+    if (MODE != 2 && mix_first) {
         if (c->nontemporal)
             hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
         else
@@ -219,17 +219,17 @@ void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const
 }
 
 template <int MODE>
-void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U, bool eq6 = false) {
+void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U, bool mix_first = false) {
     int ppb = c->ppb;
     const uint32_t nblk = (c->ntiles + FUSED_WAVES - 1) / FUSED_WAVES;
     const uint32_t gx = c->xcd_remap ? 8u * ((nblk + 7u) / 8u) : nblk;
     A.xcd_remap = c->xcd_remap;
     const dim3 grid(gx, (uint32_t)((A.n_units + ppb - 1) / ppb));
     switch (ppb) {
-        case 1: launch_fused_nt<MODE, 1>(c, P, A, U, grid, eq6); break;
-        case 2: launch_fused_nt<MODE, 2>(c, P, A, U, grid, eq6); break;
-        case 4: launch_fused_nt<MODE, 4>(c, P, A, U, grid, eq6); break;
-        default: launch_fused_nt<MODE, 8>(c, P, A, U, grid, eq6); break;
+        case 1: launch_fused_nt<MODE, 1>(c, P, A, U, grid, mix_first); break;
+        case 2: launch_fused_nt<MODE, 2>(c, P, A, U, grid, mix_first); break;
+        case 4: launch_fused_nt<MODE, 4>(c, P, A, U, grid, mix_first); break;
+        default: launch_fused_nt<MODE, 8>(c, P, A, U, grid, mix_first); break;
     }
 }
 
@@ -423,8 +423,8 @@ saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float
                           uint32_t* idx, float* msg, int64_t* K_dev, uint32_t flags) {
     if (!c) return SAPS_EINVAL;
     if (saps_status ds = check_device(c)) return ds;
-    if (flags & ~(uint32_t)SAPS_ROUND_EQ6_ORDER) return fail(c, SAPS_EINVAL, "unknown flag");
-    const bool eq6 = (flags & SAPS_ROUND_EQ6_ORDER) != 0;
+    if (flags & ~(uint32_t)SAPS_ROUND_MIX_THEN_STEP) return fail(c, SAPS_EINVAL, "unknown flag");
+    const bool mix_first = (flags & SAPS_ROUND_MIX_THEN_STEP) != 0;
     if (!X || !peer) return fail(c, SAPS_EINVAL, "null pointer");
     if (!aligned16(X) || !aligned16(G) || !aligned16(V) || !aligned16(idx) || !aligned16(msg) ||
         (reinterpret_cast<uintptr_t>(K_dev) & 7u))
@@ -451,7 +451,7 @@ saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float
 
     if (G) {
         profile_mark(c, false);
-        if (V) launch_fused<0>(c, P, A, U, eq6); else launch_fused<1>(c, P, A, U, eq6);
+        if (V) launch_fused<0>(c, P, A, U, mix_first); else launch_fused<1>(c, P, A, U, mix_first);
         profile_mark(c, true);
     } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 1.0 / 12.0 && c->density < 0.2)) {
         // measured on 32 x 11.2 M: the walk wins around c = 8 (0.62 vs 0.72 ms); for denser masks its

@@ -450,14 +450,14 @@ __device__ __forceinline__ Operands load_unit(const FusedArgs& A, int32_t i, int
 }
 
 // Local step, message write, averaging and write-back of one unit at one lane.
-// EQ6 = false: Alg. 2 order (step, then exchange of the stepped values).
-// EQ6 = true:  Eq. (6) order (exchange the values of X_t, then subtract the step computed at X_t).
-template <int MODE, bool NT, bool EQ6>
+// MIXFIRST = false: Alg. 2 order (step, then exchange of the stepped values).
+// MIXFIRST = true:  Eq. (7) order (exchange the values of X_t, then subtract the step computed at X_t).
+template <int MODE, bool NT, bool MIXFIRST>
 __device__ __forceinline__ void finish_unit(const FusedArgs& A, Operands& o, int32_t i, int32_t p, uint32_t j0,
                                             uint32_t nval, uint32_t m, uint32_t pos0) {
     const bool paired = (p != i);
     const int64_t ei = (int64_t)i * A.ld + j0, ep = (int64_t)p * A.ld + j0;
-    if (MODE != 2 && !EQ6) {
+    if (MODE != 2 && !MIXFIRST) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             float x = o.xi[r], v = o.vi[r];
@@ -487,7 +487,7 @@ __device__ __forceinline__ void finish_unit(const FusedArgs& A, Operands& o, int
             }
         }
     }
-    if (MODE != 2 && EQ6) {
+    if (MODE != 2 && MIXFIRST) {
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             float x = o.xi[r], v = o.vi[r];
@@ -520,7 +520,7 @@ __device__ __forceinline__ void finish_unit(const FusedArgs& A, Operands& o, int
     }
 }
 
-template <int MODE, int PPB, bool NT, bool EQ6>
+template <int MODE, int PPB, bool NT, bool MIXFIRST>
 __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, FusedArgs A, Units U) {
     uint32_t blk = blockIdx.x;
     if (A.xcd_remap) {
@@ -565,7 +565,7 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
         for (int u = u_lo; u < u_hi; ++u) {
             unit_at(U, u, i, p);
             cur = load_unit<MODE, NT>(A, i, p, j0, nval);
-            finish_unit<MODE, NT, EQ6>(A, cur, i, p, j0, nval, m, pos0);
+            finish_unit<MODE, NT, MIXFIRST>(A, cur, i, p, j0, nval, m, pos0);
         }
         return;
     }
@@ -577,7 +577,7 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
             unit_at(U, u + 1, in, pn);
             nxt = load_unit<MODE, NT>(A, in, pn, j0, nval);
         }
-        finish_unit<MODE, NT, EQ6>(A, cur, i, p, j0, nval, m, pos0);
+        finish_unit<MODE, NT, MIXFIRST>(A, cur, i, p, j0, nval, m, pos0);
         if (PPB > 1) { cur = nxt; i = in; p = pn; }
     }
 }

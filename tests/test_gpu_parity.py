@@ -396,17 +396,17 @@ def test_many_workers_unit_list_in_device_memory(B, n):
     assert_bits(X.cpu().numpy(), Xo, "X")
 
 
-# ------------------------------------------------------------------ Eq. (6) ordering
+# ------------------------------------------------------------------ Eq. (7) ordering
 @pytest.mark.parametrize("n,N,ld,c", SHAPES)
 @pytest.mark.parametrize("with_v", [True, False])
-def test_eq6_order_round(B, n, N, ld, c, with_v):
+def test_mix_then_step_round(B, n, N, ld, c, with_v):
     peer = rand_peer(n, n + 2 * N, singles=1 if n > 2 else 0)
     msg_ld = (N + 3) // 4 * 4
     X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2, pad=555.0, scale=1e-3)
     V0 = rand_models(n, N, ld, 3, pad=333.0, scale=1e-3) if with_v else None
     mu = 0.9 if with_v else 0.0
     Xo = X0.copy(); Vo = None if V0 is None else V0.copy()
-    rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.1, mu, 5, 3, peer, c, msg_ld=msg_ld, eq6=True)
+    rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.1, mu, 5, 3, peer, c, msg_ld=msg_ld, mix_first=True)
     assert rc == O.OK
     outs = []
     for fused in (True, False):
@@ -415,7 +415,7 @@ def test_eq6_order_round(B, n, N, ld, c, with_v):
         msg = torch.full((n, msg_ld), -5.0, device="cuda"); Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
         with B.SapsContext(n, N, ld, msg_ld, c) as ctx:
             if fused:
-                ctx.saps_round_ex(X, G, V, 0.1, mu, 5, 3, peer, idx, msg, Kd, flags=B.ROUND_EQ6_ORDER)
+                ctx.saps_round_ex(X, G, V, 0.1, mu, 5, 3, peer, idx, msg, Kd, flags=B.ROUND_MIX_THEN_STEP)
             else:
                 ctx.saps_mask_compact(X, 5, 3, idx, msg, Kd)
                 ctx.saps_merge(X, peer, idx, msg, Kd)
@@ -509,7 +509,7 @@ def _random_case(rng):
     peer = synth.random_perfect_matching(n, rng)
     for i in rng.permutation(n)[: int(rng.integers(0, 3))]:
         p = peer[i]; peer[i], peer[p] = i, p
-    kind = str(rng.choice(["fused", "fused_nov", "eq6", "exchange_list", "exchange_walk"]))
+    kind = str(rng.choice(["fused", "fused_nov", "mix_first", "exchange_list", "exchange_walk"]))
     return n, N, ld, off, cs, peer, kind, int(rng.integers(0, 2**63)), int(rng.integers(0, 2**63))
 
 
@@ -519,12 +519,12 @@ def test_random_configurations(B, case):
     n, N, ld, off, cs, peer, kind, seed, rnd = _random_case(rng)
     msg_ld = (N + 3) // 4 * 4
     X0 = rand_models(n, N, ld, case)
-    fused = kind in ("fused", "fused_nov", "eq6")
+    fused = kind in ("fused", "fused_nov", "mix_first")
     G0 = rand_models(n, N, ld, case + 1, pad=1.5, scale=1e-2) if fused else None
-    V0 = rand_models(n, N, ld, case + 2, pad=2.5, scale=1e-2) if kind in ("fused", "eq6") else None
+    V0 = rand_models(n, N, ld, case + 2, pad=2.5, scale=1e-2) if kind in ("fused", "mix_first") else None
     mu = 0.9 if V0 is not None else 0.0
     Xo = X0.copy(); Vo = None if V0 is None else V0.copy()
-    rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.1, mu, seed, rnd, peer, cs, off, msg_ld=msg_ld, eq6=(kind == "eq6"))
+    rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.1, mu, seed, rnd, peer, cs, off, msg_ld=msg_ld, mix_first=(kind == "mix_first"))
     assert rc == O.OK
     X = dev(X0); G = None if G0 is None else dev(G0); V = None if V0 is None else dev(V0)
     idx = torch.full((max(msg_ld, 4),), -1, dtype=torch.int32, device="cuda")
@@ -537,7 +537,7 @@ def test_random_configurations(B, case):
             ctx.saps_set_tuning(B.TUNE_PAIRS_PER_BLOCK, int(rng.choice([1, 2, 4, 8])))
         if fused:
             ctx.saps_set_tuning(B.TUNE_PAIRS_PER_BLOCK, int(rng.choice([1, 2, 4, 8])))
-        ctx.saps_round_ex(X, G, V, 0.1, mu, seed, rnd, peer, idx, msg, Kd, flags=B.ROUND_EQ6_ORDER if kind == "eq6" else 0)
+        ctx.saps_round_ex(X, G, V, 0.1, mu, seed, rnd, peer, idx, msg, Kd, flags=B.ROUND_MIX_THEN_STEP if kind == "mix_first" else 0)
         assert ctx.saps_poll_status() == (0, K), (kind, n, N)
     assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K]), kind
     assert np.all(idx.cpu().numpy()[K:] == -1)

@@ -45,7 +45,7 @@ MISTAKES = [
     if (rc) return rc;
     if (G) rc = oracle_sgd_step(n, N, ld, X, G, V, lr, mu);
     return rc;"""),
-    ("Eq. (6) order steps first", """    if (rc) return rc;                                  // capacity overflow: nothing was written
+    ("Eq. (7) order steps first", """    if (rc) return rc;                                  // capacity overflow: nothing was written
     rc = oracle_merge(n, N, ld, X, peer, idx, msg, msg_ld, *K_out);
     if (rc) return rc;
     if (G) rc = oracle_sgd_step(n, N, ld, X, G, V, lr, mu);
@@ -59,17 +59,70 @@ MISTAKES = [
     ("disagreement without the square", "row += d * d;", "row += d < 0 ? -d : d;"),
 ]
 
+# The per-segment loop appears four times in the oracle (mask; count and fill of the compaction; count of
+# the round).  Each site gets each slip on its own: (name, old, new, which occurrence of `old`).
+_T = "const uint64_t T = threshold(seg_c[s]);"
+_LOOP = "for (int64_t j = seg_off[s]; j < seg_off[s + 1]; ++j)"
+_SEGS = "for (int s = 0; s < n_seg; ++s) {\n        const uint64_t T"
+_SITES = ["mask", "compaction count", "compaction fill", "round count"]
+SEGMENT_MISTAKES = []
+for k, site in enumerate(_SITES):
+    SEGMENT_MISTAKES += [
+        (f"{site}: first segment's ratio for every segment", _T, "const uint64_t T = threshold(seg_c[0]);", k),
+        (f"{site}: next segment's ratio", _T, "const uint64_t T = threshold(seg_c[s + 1 < n_seg ? s + 1 : s]);", k),
+        (f"{site}: segment starts one late", _LOOP, "for (int64_t j = seg_off[s] + 1; j < seg_off[s + 1]; ++j)", k),
+        (f"{site}: segment ends one early", _LOOP, "for (int64_t j = seg_off[s]; j + 1 < seg_off[s + 1]; ++j)", k),
+        (f"{site}: last segment skipped", _SEGS, "for (int s = 0; s + 1 < n_seg || s == 0; ++s) {\n        const uint64_t T", k),
+    ]
+# "<=" at a segment end: every cut is decided twice, once with the wrong ratio.  Planted where the extra
+# coordinate cannot run past a buffer (the two counting loops and the mask are pure reads/own array of N).
+SEGMENT_MISTAKES += [
+    ("compaction count: <= at the segment end", _LOOP, "for (int64_t j = seg_off[s]; j <= seg_off[s + 1] && j < N; ++j)", 1),
+    ("compaction fill: <= at the segment end", _LOOP, "for (int64_t j = seg_off[s]; j <= seg_off[s + 1] && j < N && k < K; ++j)", 2),
+    ("round count: <= at the segment end", _LOOP, "for (int64_t j = seg_off[s]; j <= seg_off[s + 1] && j < N; ++j)", 3),
+]
+
+
+def _replace_nth(text, old, new, k):
+    pos = -1
+    for _ in range(k + 1):
+        pos = text.find(old, pos + 1)
+        assert pos >= 0, "mutation site not found"
+    return text[:pos] + new + text[pos + len(old):]
+
+
+PIN_FILES = ["test_oracle_mask.py", "test_oracle_round.py", "test_oracle_segments.py"]
+
+
+def _pins_reject(mutant_text, name):
+    with tempfile.TemporaryDirectory() as tmp:
+        src = os.path.join(tmp, "mutant.cpp"); lib = os.path.join(tmp, "libmutant.so")
+        open(src, "w").write(mutant_text)
+        subprocess.run(["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-mfma", "-shared", "-fPIC", src, "-o", lib], check=True)
+        env = dict(os.environ, SAPS_ORACLE_LIB=lib, SAPS_ORACLE_MUTATION_RUN="1")
+        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
+                            *[os.path.join(ROOT, "tests", f) for f in PIN_FILES]],
+                           env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
+        assert r.returncode == 1, f"pin suite exit code {r.returncode} (1 = a pin failed) for: {name}\n{r.stdout[-800:]}"
+
 
 @pytest.mark.parametrize("name,old,new", MISTAKES, ids=[m[0] for m in MISTAKES])
 def test_pin_suite_rejects_a_planted_mistake(name, old, new):
     text = open(SRC).read()
     assert text.count(old) == 1, f"mutation site for '{name}' must occur exactly once in the oracle source"
-    with tempfile.TemporaryDirectory() as tmp:
-        src = os.path.join(tmp, "mutant.cpp"); lib = os.path.join(tmp, "libmutant.so")
-        open(src, "w").write(text.replace(old, new))
-        subprocess.run(["g++", "-O2", "-std=c++17", "-ffp-contract=off", "-mfma", "-shared", "-fPIC", src, "-o", lib], check=True)
-        env = dict(os.environ, SAPS_ORACLE_LIB=lib)
-        r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                            os.path.join(ROOT, "tests", "test_oracle_mask.py"), os.path.join(ROOT, "tests", "test_oracle_round.py")],
-                           env=env, cwd=ROOT, capture_output=True, text=True, timeout=300)
-        assert r.returncode == 1, f"pin suite exit code {r.returncode} (1 = a pin failed) for: {name}\n{r.stdout[-800:]}"
+    _pins_reject(text.replace(old, new), name)
+
+
+@pytest.mark.parametrize("name,old,new,k", SEGMENT_MISTAKES, ids=[m[0] for m in SEGMENT_MISTAKES])
+def test_pin_suite_rejects_a_slip_in_a_segment_loop(name, old, new, k):
+    text = open(SRC).read()
+    assert text.count(old) == len(_SITES), "the oracle's four segment loops changed shape: update the sites"
+    _pins_reject(_replace_nth(text, old, new, k), name)
+
+
+def test_the_oracle_override_needs_the_mutation_marker():
+    # a stray SAPS_ORACLE_LIB alone must not swap the checker under any test
+    env = {k: v for k, v in os.environ.items() if k != "SAPS_ORACLE_MUTATION_RUN"}
+    env["SAPS_ORACLE_LIB"] = "/nonexistent/libother.so"
+    r = subprocess.run([sys.executable, "-c", "from oracle import saps_oracle"], env=env, cwd=ROOT, capture_output=True, text=True)
+    assert r.returncode != 0 and "SAPS_ORACLE_MUTATION_RUN" in r.stderr

@@ -39,7 +39,7 @@ def test_exchange_invariants(case):
     keep = np.array([IP.keep(seed, rnd, j, c) for j in range(N)], dtype=bool)
     assert K == int(keep.sum()) and np.array_equal(idx[:K], np.flatnonzero(keep).astype(np.uint32))
     assert np.array_equal(msg[:, :K], X0[:, keep])
-    assert np.array_equal(X[:, ~keep], X0[:, ~keep])                     # Eq. (6): X o notM untouched
+    assert np.array_equal(X[:, ~keep], X0[:, ~keep])                     # Eq. (7): X o notM untouched
     for i in range(n):
         p = int(peer[i])
         if p == i:
@@ -54,22 +54,22 @@ def test_exchange_invariants(case):
 
 @settings(max_examples=80, deadline=None)
 @given(cases(), st.floats(0.0, 0.5), st.floats(0.0, 0.95), st.booleans())
-def test_round_is_step_then_exchange_or_exchange_then_step(case, lr, mu, eq6):
+def test_round_is_step_then_exchange_or_exchange_then_step(case, lr, mu, mix_first):
     n, N, c, seed, rnd, peer, data_seed = case
     rng = np.random.default_rng(data_seed)
     X0 = rng.standard_normal((n, N)).astype(np.float32); G = rng.standard_normal((n, N)).astype(np.float32)
     V0 = rng.standard_normal((n, N)).astype(np.float32)
     X, V = X0.copy(), V0.copy()
-    rc, K, idx, msg = O.round_(X, G, V, N, lr, mu, seed, rnd, peer, float(c), eq6=eq6)
+    rc, K, idx, msg = O.round_(X, G, V, N, lr, mu, seed, rnd, peer, float(c), mix_first=mix_first)
     assert rc == O.OK
     # the same result from the single-stage entries in the stated order
     Y, W = X0.copy(), V0.copy()
-    if not eq6:
+    if not mix_first:
         O.sgd_step(Y, G, W, lr, mu)
     rc2, K2, idx2, msg2 = O.mask_compact(Y, N, seed, rnd, float(c))
     assert (rc2, K2) == (O.OK, K)
     O.merge(Y, N, peer, idx2, msg2, K2)
-    if eq6:
+    if mix_first:
         O.sgd_step(Y, G, W, lr, mu)
     assert np.array_equal(X.view(np.uint32), Y.view(np.uint32)) and np.array_equal(V.view(np.uint32), W.view(np.uint32))
     assert np.array_equal(msg[:, :K].view(np.uint32), msg2[:, :K].view(np.uint32))

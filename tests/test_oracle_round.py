@@ -1,7 +1,7 @@
 """Pins of the oracle's update, compaction, merge and round — CPU only.
 
 Nothing here re-calls the oracle to check the oracle: expected values come from the
-explicit matrices of Eq. (6), from numpy/torch library routines, from closed forms, or
+explicit matrices of Eq. (7), from numpy/torch library routines, from closed forms, or
 from invariants the paper states (doubly stochastic W, Lemma 1, Lemma 2).
 """
 import itertools
@@ -34,7 +34,7 @@ def _matchings4():
     return [[1, 0, 3, 2], [2, 3, 0, 1], [3, 2, 1, 0], [0, 1, 2, 3], [1, 0, 2, 3], [0, 3, 2, 1]]
 
 
-# ---------------------------------------------------------------- brute force, Eq. (6)
+# ---------------------------------------------------------------- brute force, Eq. (7)
 @pytest.mark.parametrize("n,N", [(2, 1), (2, 7), (3, 13), (4, 64), (4, 61)])
 @pytest.mark.parametrize("c", [1, 2, 4])
 def test_exchange_equals_explicit_matrix_form(n, N, c):
@@ -320,9 +320,9 @@ def test_dense_pair_averaging_lowers_disagreement_by_half_the_pair_distances():
     assert abs(D1 - (D0 - 0.5 * pair)) <= 1e-12 * D0
 
 
-# ------------------------------------------------------------------- Eq. (6) ordering
+# ------------------------------------------------------------------- Eq. (7) ordering
 @pytest.mark.parametrize("c", [1, 2, 4])
-def test_eq6_order_equals_explicit_matrix_form_with_gradient_term(c):
+def test_mix_then_step_order_equals_explicit_matrix_form_with_gradient_term(c):
     # X_{t+1} = X o notM + (X o M) W - gamma G(X_t), plain SGD (no momentum buffer)
     n, N = 4, 64
     rng = np.random.default_rng(31 + c)
@@ -336,13 +336,13 @@ def test_eq6_order_equals_explicit_matrix_form_with_gradient_term(c):
         mixed = (Xp * (1 - M) + (Xp * M) @ _W(peer)).T.astype(np.float32)          # exact halves, one rounding
         want = (mixed.astype(np.float64) - np.float64(lr) * G.astype(np.float64)).astype(np.float32)
         got = X.copy()
-        rc, K, idx, msg = O.round_(got, G, None, N, float(lr), 0.0, 5, rnd, np.array(peer), float(c), eq6=True)
+        rc, K, idx, msg = O.round_(got, G, None, N, float(lr), 0.0, 5, rnd, np.array(peer), float(c), mix_first=True)
         assert rc == O.OK and K == int(m.sum())
         assert np.array_equal(msg[:, :K], X[:, m])                                  # messages carry X_t
         assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
 
 
-def test_eq6_and_alg2_orders_differ_only_on_masked_coordinates_of_matched_rows():
+def test_mix_then_step_and_alg2_orders_differ_only_on_masked_coordinates_of_matched_rows():
     n, N = 4, 2000
     rng = np.random.default_rng(40)
     X = rng.standard_normal((n, N)).astype(np.float32); G = rng.standard_normal((n, N)).astype(np.float32)
@@ -350,14 +350,50 @@ def test_eq6_and_alg2_orders_differ_only_on_masked_coordinates_of_matched_rows()
     peer = np.array([1, 0, 2, 3])                                                  # rows 2, 3 unmatched
     A, VA, Bm, VB = X.copy(), V.copy(), X.copy(), V.copy()
     _, K, idx, _ = O.round_(A, G, VA, N, 0.1, 0.9, 7, 1, peer, 4.0)
-    O.round_(Bm, G, VB, N, 0.1, 0.9, 7, 1, peer, 4.0, eq6=True)
+    O.round_(Bm, G, VB, N, 0.1, 0.9, 7, 1, peer, 4.0, mix_first=True)
     m = np.zeros(N, bool); m[idx[:K]] = True
     assert np.array_equal(VA, VB)                                                   # the buffer never sees the exchange
     assert np.array_equal(A[:, ~m], Bm[:, ~m]) and np.array_equal(A[2:], Bm[2:])
     assert not np.array_equal(A[:2, m], Bm[:2, m])
-    # under Eq. (6) the pair keeps a difference of gamma * (v_p - v_i) on masked coordinates; under Alg. 2 none
+    # under Eq. (7) the pair keeps a difference of gamma * (v_p - v_i) on masked coordinates; under Alg. 2 none
     assert np.array_equal(A[0, m], A[1, m]) and not np.array_equal(Bm[0, m], Bm[1, m])
     # without gradients both orders are the same exchange
     C1, C2 = X.copy(), X.copy()
-    O.round_(C1, None, None, N, 0, 0, 7, 1, peer, 4.0); O.round_(C2, None, None, N, 0, 0, 7, 1, peer, 4.0, eq6=True)
+    O.round_(C1, None, None, N, 0, 0, 7, 1, peer, 4.0); O.round_(C2, None, None, N, 0, 0, 7, 1, peer, 4.0, mix_first=True)
     assert np.array_equal(C1, C2)
+
+
+# ------------------------------------------------- several local steps between exchanges
+@pytest.mark.parametrize("mix_first", [False, True], ids=["alg2_order", "recursion_order"])
+def test_tau_local_steps_then_one_exchange_equals_explicit_matrix_form(mix_first):
+    # Communication period tau = 3: two rounds with W = I (a worker that only runs procedure SGD of Alg. 2)
+    # and one round with the matching's W.  Composition used by callers: (tau - 1) x sgd_step, then round.
+    n, N, c, tau = 4, 64, 2, 3
+    rng = np.random.default_rng(55)
+    lr = np.float32(0.125)
+    for rnd, peer in enumerate(_matchings4(), start=1):
+        X = rng.standard_normal((n, N)).astype(np.float32)
+        Gs = [rng.standard_normal((n, N)).astype(np.float32) for _ in range(tau)]
+        m = _mask_indep(N, 6, rnd, c)
+        M = np.repeat(m[:, None], n, axis=1).astype(np.float64)
+        W = _W(peer)
+        step = lambda A, G: (A.astype(np.float64) - np.float64(lr) * G.astype(np.float64)).astype(np.float32)
+        mix = lambda A: (A.T.astype(np.float64) * (1 - M) + (A.T.astype(np.float64) * M) @ W).T.astype(np.float32)
+        want = X
+        for G in Gs[:-1]:
+            want = step(want, G)                                  # X o notM + (X o M) I - gamma G = X - gamma G
+        sent = want if mix_first else step(want, Gs[-1])
+        want = step(mix(want), Gs[-1]) if mix_first else mix(step(want, Gs[-1]))
+        got = X.copy()
+        for G in Gs[:-1]:
+            assert O.sgd_step(got, G, None, float(lr), 0.0) == O.OK
+        rc, K, idx, msg = O.round_(got, Gs[-1], None, N, float(lr), 0.0, 6, rnd, np.array(peer), float(c), mix_first=mix_first)
+        assert rc == O.OK and K == int(m.sum())
+        assert np.array_equal(msg[:, :K], sent[:, m])
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32))
+        # the same thing said with rounds only: an identity matching is a round without exchange
+        alt = X.copy()
+        for G in Gs[:-1]:
+            O.round_(alt, G, None, N, float(lr), 0.0, 6, 1000 + rnd, np.arange(n), float(c), mix_first=mix_first)
+        O.round_(alt, Gs[-1], None, N, float(lr), 0.0, 6, rnd, np.array(peer), float(c), mix_first=mix_first)
+        assert np.array_equal(alt.view(np.uint32), want.view(np.uint32))

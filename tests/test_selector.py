@@ -48,6 +48,57 @@ def test_oracle_components_match_scipy():
         assert len({(a, b) for a, b in zip(lab, lab2)}) == k
 
 
+def test_oracle_graph_pieces_on_a_hand_worked_five_worker_example():
+    # Worked by hand from Sec. II-C and Alg. 1 / Alg. 3: speeds measured in both directions, the slower one counts.
+    Braw = np.array([[0, 9, 2, 7, 1],
+                     [5, 0, 8, 3, 6],
+                     [4, 8, 0, 2, 9],
+                     [7, 1, 6, 0, 3],
+                     [2, 6, 5, 4, 0]], dtype=np.float64)
+    S = np.array([[0, 5, 2, 7, 1],
+                  [5, 0, 8, 1, 6],
+                  [2, 8, 0, 2, 5],
+                  [7, 1, 2, 0, 3],
+                  [1, 6, 5, 3, 0]], dtype=np.float64)
+    assert np.array_equal(PO.symmetrise(Braw), S)
+    # B_thres = 5 keeps the links (0,1) (0,3) (1,2) (1,4) (2,4); the threshold itself counts as fast enough
+    Bstar = np.zeros((5, 5), np.uint8)
+    for a, b in [(0, 1), (0, 3), (1, 2), (1, 4), (2, 4)]:
+        Bstar[a, b] = Bstar[b, a] = 1
+    assert np.array_equal(PO.filtered_graph(Braw, 5.0), Bstar)
+    assert PO.filtered_graph(Braw, 5.000001).sum() == 2 * 3          # (0,1) and (2,4) drop out
+    # timestamps at round t = 10: (0,1) used in round 9, (2,3) in 7, (1,2) in 6, (0,4) in 2, the rest never
+    R = np.full((5, 5), PO.NEVER, dtype=np.int64)
+    for (a, b), r in {(0, 1): 9, (2, 3): 7, (1, 2): 6, (0, 4): 2}.items():
+        R[a, b] = R[b, a] = r
+
+    def graph(edges):
+        Q = np.zeros((5, 5), np.uint8)
+        for a, b in edges:
+            Q[a, b] = Q[b, a] = 1
+        return Q
+    # window 4: recent means used after round 6, so (1,2) has just expired
+    assert np.array_equal(PO.recently_connected(R, 4, 10), graph([(0, 1), (2, 3)]))
+    connected, ncomp, E = PO.candidate_matrix(Bstar, R, 4, 10)
+    assert not connected and ncomp == 3                              # {0,1} {2,3} {4}
+    assert np.array_equal(E, graph([(0, 2), (0, 3), (0, 4), (1, 2), (1, 3), (1, 4), (2, 4), (3, 4)]))
+    assert PO.max_matching_size(E) == 2
+    # window 5: (1,2) still counts, components {0,1,2,3} {4}: only links to worker 4 join two components
+    assert np.array_equal(PO.recently_connected(R, 5, 10), graph([(0, 1), (2, 3), (1, 2)]))
+    connected, ncomp, E = PO.candidate_matrix(Bstar, R, 5, 10)
+    assert not connected and ncomp == 2
+    assert np.array_equal(E, graph([(0, 4), (1, 4), (2, 4), (3, 4)]))
+    assert PO.max_matching_size(E) == 1
+    # window 9: (0,4) from round 2 counts too, everyone is connected, so the fast links B* are the candidates
+    assert np.array_equal(PO.recently_connected(R, 9, 10), graph([(0, 1), (2, 3), (1, 2), (0, 4)]))
+    connected, ncomp, E = PO.candidate_matrix(Bstar, R, 9, 10)
+    assert connected and ncomp == 1 and np.array_equal(E, Bstar)
+    assert PO.max_matching_size(E) == 2                              # e.g. (0,3) (1,2) or (0,3) (2,4)
+    # nothing ever used: five isolated workers, every pair is a candidate
+    connected, ncomp, E = PO.candidate_matrix(Bstar, np.full((5, 5), PO.NEVER, dtype=np.int64), 4, 1)
+    assert not connected and ncomp == 5 and E.sum() == 20 and not E.diagonal().any()
+
+
 # ------------------------------------------------------------ maximum matching (blossom)
 @pytest.mark.parametrize("n", [1, 2, 3, 5, 8, 11, 14])
 def test_max_matching_is_maximum_and_valid_on_random_graphs(n):
