@@ -112,6 +112,27 @@ saps_status saps_round_ex(saps_ctx* ctx, float* X, const float* G, float* V, flo
                           uint64_t seed, uint64_t round, const int32_t* peer,
                           uint32_t* idx, float* msg, int64_t* K_dev, uint32_t flags);
 
+/* For callers that cannot allocate device memory: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  saps_round() without a context, for a model with ONE compression
+ * ratio c (the paper's case, n_seg = 1): the private scratch that saps_create() would allocate (tile and
+ * group counts, K, an index list) lives in a fixed device array inside the library instead, about 3.1 MiB
+ * per GPU the library runs on, held until the process ends.  Calls no hipMalloc / hipFree and nothing
+ * that allocates; only kernels are enqueued on hip_stream (no memset, no copy, no event), so a call can
+ * be recorded into a graph.  The first call on a device looks up that device's copy of the array
+ * (hipGetSymbolAddress): make one call outside a capture first.
+ *   Arguments as saps_round(); n, N, ld, c, msg_ld as in saps_layout / saps_create().
+ *   Limits (SAPS_EINVAL beyond them): N <= 67,108,864; at most 128 units in the matching (pairs plus
+ *   unmatched workers, i.e. n <= 256 when everyone is matched); K_dev must not be NULL (there is no context
+ *   to poll: *K_dev > msg_ld tells the caller that the round was skipped and nothing was written);
+ *   idx == NULL needs msg_ld <= 524,288.
+ *   All calls on one GPU share the one scratch array: calls that overlap on a GPU (two streams, two
+ *   threads) race.  Results are bit-identical to saps_round() on a context of the same layout.
+ *   Error text: saps_last_error(NULL) (per thread). */
+saps_status saps_round_static(int32_t n, int64_t N, int64_t ld, double c, int64_t msg_ld, void* hip_stream,
+                              float* X, const float* G, float* V, float lr, float mu,
+                              uint64_t seed, uint64_t round, const int32_t* peer,
+                              uint32_t* idx, float* msg, int64_t* K_dev);
+
 /* Consensus diagnostics (Sec. II-C: consensus means that the workers' distance to the average
  * model goes to zero; Theorem 1 bounds sum_i ||mean - x_i||^2).  Writes the average model
  * mean_out[j] = (1/n) sum_i X[i][j] (device, N floats, may be NULL) and the total disagreement
@@ -124,7 +145,8 @@ saps_status saps_consensus(saps_ctx* ctx, const float* X, float* mean_out, doubl
  * receives the K of the most recent mask generation. */
 saps_status saps_poll_status(saps_ctx* ctx, int64_t* K_host);
 
-/* Text of the last host-side error on this context (never NULL). */
+/* Text of the last host-side error on this context (never NULL); ctx == NULL gives the calling
+ * thread's last saps_round_static() error. */
 const char* saps_last_error(const saps_ctx* ctx);
 
 /* Launch-shape knobs for measurement sweeps; results never depend on them.

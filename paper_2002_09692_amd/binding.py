@@ -22,7 +22,7 @@ _NAMES = {OK: "SAPS_OK", EINVAL: "SAPS_EINVAL", EMATCH: "SAPS_EMATCH", ECAPACITY
 
 EXPORTS = ("saps_abi_version", "saps_create", "saps_destroy", "saps_sgd_step", "saps_mask_compact", "saps_merge",
            "saps_round", "saps_poll_status", "saps_last_error", "saps_set_tuning", "saps_stream_copy",
-           "saps_profile_enable", "saps_profile_read", "saps_consensus", "saps_round_ex")
+           "saps_profile_enable", "saps_profile_read", "saps_consensus", "saps_round_ex", "saps_round_static")
 
 
 class SapsError(RuntimeError):
@@ -62,6 +62,8 @@ def load_library() -> C.CDLL:
     L.saps_stream_copy.argtypes = [vp, vp, vp, i64]; L.saps_stream_copy.restype = C.c_int
     L.saps_round_ex.argtypes = [vp, vp, vp, vp, f32, f32, u64, u64, vp, vp, vp, vp, C.c_uint32]; L.saps_round_ex.restype = C.c_int
     L.saps_consensus.argtypes = [vp, vp, vp, vp]; L.saps_consensus.restype = C.c_int
+    L.saps_round_static.argtypes = [i32, i64, i64, C.c_double, i64, vp, vp, vp, vp, f32, f32, u64, u64, vp, vp, vp, vp]
+    L.saps_round_static.restype = C.c_int
     L.saps_profile_enable.argtypes = [vp, i32]; L.saps_profile_enable.restype = C.c_int
     L.saps_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]; L.saps_profile_read.restype = C.c_int
     _lib = L
@@ -140,6 +142,30 @@ def saps_max_matching(E: np.ndarray, seed: int = 0):
     peer = np.empty(n, dtype=np.int32)
     pairs = L.saps_max_matching(n, Ec.ctypes.data_as(C.c_void_p), seed, peer.ctypes.data_as(C.c_void_p))
     return int(pairs), peer
+
+
+def saps_round_static(n: int, N: int, ld: int, c: float, msg_ld: int, X, G, V, lr: float, mu: float, seed: int, rnd: int,
+                      peer, idx=None, msg=None, K_dev=None, stream: Optional[torch.cuda.Stream] = None, check: bool = True) -> int:
+    """saps_round without a context, on the library's fixed scratch (for callers that cannot allocate)."""
+    L = load_library()
+    p = _peer(peer)
+    if p.shape != (n,):
+        raise ValueError("peer: need n entries")
+    for t, name in ((X, "X"), (G, "G"), (V, "V")):
+        if t is not None and tuple(t.shape) != (n, ld):
+            raise ValueError(f"{name}: shape {tuple(t.shape)} != {(n, ld)}")
+    if msg is not None and tuple(msg.shape) != (n, msg_ld):
+        raise ValueError("msg: shape")
+    if idx is not None and idx.numel() < msg_ld:
+        raise ValueError("idx: fewer than msg_ld entries")
+    st = stream if stream is not None else torch.cuda.current_stream()
+    rc = L.saps_round_static(n, N, ld, float(c), msg_ld, C.c_void_p(st.cuda_stream), _dev(X, torch.float32, "X"),
+                             _dev(G, torch.float32, "G"), _dev(V, torch.float32, "V"), lr, mu, seed, rnd,
+                             p.ctypes.data_as(C.c_void_p), _dev(idx, torch.int32, "idx"), _dev(msg, torch.float32, "msg"),
+                             _dev(K_dev, torch.int64, "K_dev"))
+    if check and rc != OK:
+        raise SapsError(rc, L.saps_last_error(None).decode())
+    return rc
 
 
 class SapsContext:

@@ -6,6 +6,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <vector>
@@ -26,6 +27,28 @@ struct Slot {
     hipEvent_t done = nullptr;
     bool used = false;
 };
+
+// Scratch of saps_round_static(), the entry point for callers that cannot allocate: tile and group
+// counts, K, the capacity flag and an index list, in one file-scope device array instead of a context's
+// hipMalloc'd buffers.  Every GPU the library runs on holds its own copy (about 3.1 MiB) until the
+// process ends.  In host code the array's name is only a handle for hipGetSymbolAddress(): the address
+// that kernels and copies may use is the one that call returns, kept per device in g_static_ptr.
+constexpr int64_t STATIC_MAX_N = 1ll << 26;                                   // 67,108,864 coordinates
+constexpr uint32_t STATIC_MAX_TILES = (uint32_t)(STATIC_MAX_N / TILE);
+constexpr uint32_t STATIC_MAX_GROUPS = STATIC_MAX_TILES / GROUP;
+constexpr int64_t STATIC_MAX_LIST = 1ll << 19;                                // entries of the internal index list
+constexpr size_t ST_OFF_K = 0, ST_OFF_FLAG = 64;
+constexpr size_t ST_OFF_TILE = 256;
+constexpr size_t ST_OFF_GRP = ST_OFF_TILE + sizeof(uint32_t) * ((size_t)STATIC_MAX_TILES + 64);
+constexpr size_t ST_OFF_IDX = ST_OFF_GRP + sizeof(uint32_t) * ((size_t)STATIC_MAX_GROUPS + 64);
+constexpr size_t ST_BYTES = ST_OFF_IDX + sizeof(uint32_t) * (size_t)STATIC_MAX_LIST;
+static_assert(ST_OFF_GRP % 256 == 0 && ST_OFF_IDX % 256 == 0, "scratch parts stay 256-byte aligned");
+static __device__ __align__(256) unsigned char scratch[ST_BYTES];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+std::mutex g_static_mu;
+unsigned char* g_static_ptr[STATIC_MAX_DEVICES] = {};
+thread_local std::string g_static_err;
 
 }  // namespace
 
@@ -130,6 +153,7 @@ saps_status make_units(saps_ctx* c, const int32_t* peer, Units* U, int32_t* n_un
         for (; k < MAX_INLINE_UNITS; ++k) U->packed[k] = 0u;
         return SAPS_OK;
     }
+    if (!c->ring[0].host) return fail(c, SAPS_EINVAL, "the matching has more than 128 units");
     Slot& s = c->ring[c->calls++ % RING];
     if (s.used) SAPS_HIP(c, hipEventSynchronize(s.done));
     int32_t* units = s.host;
@@ -233,13 +257,67 @@ void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U
     }
 }
 
+// Argument checks and launch sequence of one round; `c` is a created context or the stack-built
+// description that saps_round_static() fills from its arguments.
+saps_status round_impl(saps_ctx* c, float* X, const float* G, float* V, float lr, float mu,
+                       uint64_t seed, uint64_t round, const int32_t* peer,
+                       uint32_t* idx, float* msg, int64_t* K_dev, uint32_t flags) {
+    if (flags & ~(uint32_t)SAPS_ROUND_MIX_THEN_STEP) return fail(c, SAPS_EINVAL, "unknown flag");
+    const bool mix_first = (flags & SAPS_ROUND_MIX_THEN_STEP) != 0;
+    if (!X || !peer) return fail(c, SAPS_EINVAL, "null pointer");
+    if (!aligned16(X) || !aligned16(G) || !aligned16(V) || !aligned16(idx) || !aligned16(msg) ||
+        (reinterpret_cast<uintptr_t>(K_dev) & 7u))
+        return fail(c, SAPS_EINVAL, "misaligned pointer");
+    if (G && !V && mu != 0.0f) return fail(c, SAPS_EINVAL, "momentum needs V");
+    if (!matching_ok(c->n, peer)) return fail(c, SAPS_EMATCH, "peer[] is not an involution of [0, n)");
+    int32_t n_units = 0;
+    Units U;
+    saps_status s = make_units(c, peer, &U, &n_units);
+    if (s) return s;
+    const MaskParams P = mask_params(c, seed, round);
+    Bases Bp;
+    s = enqueue_count_scan(c, P, K_dev, &Bp);
+    if (s) return s;
+    if (c->ntiles == 0) return SAPS_OK;
+
+    FusedArgs A;
+    A.X = X; A.G = G; A.V = V; A.ld = c->ld;
+    A.n_units = n_units;
+    A.lr = lr; A.mu = mu;
+    A.bases = Bp;
+    A.idx = idx; A.msg = msg; A.msg_ld = c->msg_ld;
+    A.ntiles = c->ntiles; A.xcd_remap = 0;
+
+    if (G) {
+        profile_mark(c, false);
+        if (V) launch_fused<0>(c, P, A, U, mix_first); else launch_fused<1>(c, P, A, U, mix_first);
+        profile_mark(c, true);
+    } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 1.0 / 12.0 && c->density < 0.2)) {
+        // measured on 32 x 11.2 M: the walk wins around c = 8 (0.62 vs 0.72 ms); for denser masks its
+        // per-lane message stores cost more than the list's coalesced ones (c = 2, 4: 0.82-0.86 vs 0.73 ms)
+        profile_mark(c, false);
+        launch_fused<2>(c, P, A, U);                   // dense masks: walk the tiles
+        profile_mark(c, true);
+    } else {
+        uint32_t* list = idx ? idx : c->d_idx;        // sparse masks: go through the index list
+        hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, Bp, list);
+        profile_mark(c, false);
+        hipLaunchKernelGGL(exchange_list_kernel, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
+                           X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);
+        profile_mark(c, true);
+    }
+    SAPS_HIP(c, hipGetLastError());
+    return SAPS_OK;
+}
+
 }  // namespace
 
 extern "C" {
 
-int32_t saps_abi_version(void) { return 2; }
+int32_t saps_abi_version(void) { return 3; }
 
-const char* saps_last_error(const saps_ctx* ctx) { return ctx ? ctx->err.c_str() : "null context"; }
+// ctx == NULL: the calling thread's last saps_round_static() error
+const char* saps_last_error(const saps_ctx* ctx) { return ctx ? ctx->err.c_str() : g_static_err.c_str(); }
 
 saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, void* hip_stream) {
     if (!out) return SAPS_EINVAL;
@@ -423,52 +501,60 @@ saps_status saps_round_ex(saps_ctx* c, float* X, const float* G, float* V, float
                           uint32_t* idx, float* msg, int64_t* K_dev, uint32_t flags) {
     if (!c) return SAPS_EINVAL;
     if (saps_status ds = check_device(c)) return ds;
-    if (flags & ~(uint32_t)SAPS_ROUND_MIX_THEN_STEP) return fail(c, SAPS_EINVAL, "unknown flag");
-    const bool mix_first = (flags & SAPS_ROUND_MIX_THEN_STEP) != 0;
-    if (!X || !peer) return fail(c, SAPS_EINVAL, "null pointer");
-    if (!aligned16(X) || !aligned16(G) || !aligned16(V) || !aligned16(idx) || !aligned16(msg) ||
-        (reinterpret_cast<uintptr_t>(K_dev) & 7u))
-        return fail(c, SAPS_EINVAL, "misaligned pointer");
-    if (G && !V && mu != 0.0f) return fail(c, SAPS_EINVAL, "momentum needs V");
-    if (!matching_ok(c->n, peer)) return fail(c, SAPS_EMATCH, "peer[] is not an involution of [0, n)");
-    int32_t n_units = 0;
-    Units U;
-    saps_status s = make_units(c, peer, &U, &n_units);
-    if (s) return s;
-    const MaskParams P = mask_params(c, seed, round);
-    Bases Bp;
-    s = enqueue_count_scan(c, P, K_dev, &Bp);
-    if (s) return s;
-    if (c->ntiles == 0) return SAPS_OK;
+    return round_impl(c, X, G, V, lr, mu, seed, round, peer, idx, msg, K_dev, flags);
+}
 
-    FusedArgs A;
-    A.X = X; A.G = G; A.V = V; A.ld = c->ld;
-    A.n_units = n_units;
-    A.lr = lr; A.mu = mu;
-    A.bases = Bp;
-    A.idx = idx; A.msg = msg; A.msg_ld = c->msg_ld;
-    A.ntiles = c->ntiles; A.xcd_remap = 0;
+saps_status saps_round_static(int32_t n, int64_t N, int64_t ld, double c_ratio, int64_t msg_ld, void* hip_stream,
+                              float* X, const float* G, float* V, float lr, float mu,
+                              uint64_t seed, uint64_t round, const int32_t* peer,
+                              uint32_t* idx, float* msg, int64_t* K_dev) {
+    auto bad = [](const char* what) { g_static_err = what; return SAPS_EINVAL; };
+    if (n < 1 || n > MAX_WORKERS || N < 0 || ld < N || (ld & 3) || msg_ld < 0 || (msg_ld & 3)) return bad("bad n, N, ld or msg_ld");
+    if (N > STATIC_MAX_N) return bad("N exceeds the static scratch (at most 67,108,864 coordinates)");
+    if (!(c_ratio >= 1.0)) return bad("compression ratio below 1");
+    if (!K_dev) return bad("K_dev is required: it is how the caller sees that K > msg_ld skipped the round");
+    if (!idx && msg_ld > STATIC_MAX_LIST) return bad("idx == NULL needs msg_ld <= 524,288 (the internal index list)");
+    if (!peer) return bad("null pointer");
+    int32_t units = 0;
+    for (int32_t i = 0; i < n; ++i) units += (peer[i] >= i);
+    if (units > MAX_INLINE_UNITS) return bad("the matching has more than 128 units (pairs plus unmatched workers)");
 
-    if (G) {
-        profile_mark(c, false);
-        if (V) launch_fused<0>(c, P, A, U, mix_first); else launch_fused<1>(c, P, A, U, mix_first);
-        profile_mark(c, true);
-    } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 1.0 / 12.0 && c->density < 0.2)) {
-        // measured on 32 x 11.2 M: the walk wins around c = 8 (0.62 vs 0.72 ms); for denser masks its
-        // per-lane message stores cost more than the list's coalesced ones (c = 2, 4: 0.82-0.86 vs 0.73 ms)
-        profile_mark(c, false);
-        launch_fused<2>(c, P, A, U);                   // dense masks: walk the tiles
-        profile_mark(c, true);
-    } else {
-        uint32_t* list = idx ? idx : c->d_idx;        // sparse masks: go through the index list
-        hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, Bp, list);
-        profile_mark(c, false);
-        hipLaunchKernelGGL(exchange_list_kernel, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
-                           X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);
-        profile_mark(c, true);
+    // the device's own copy of the scratch array: resolved once per device, with that device current
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) { g_static_err = "hipGetDevice"; return SAPS_EHIP; }
+    unsigned char* base = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_static_mu);
+        if (!g_static_ptr[dev]) {
+            void* ptr = nullptr;
+            const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+            if (e != hipSuccess || !ptr) {
+                g_static_err = std::string("hipGetSymbolAddress(scratch): ") + hipGetErrorString(e);
+                return SAPS_EHIP;
+            }
+            g_static_ptr[dev] = static_cast<unsigned char*>(ptr);
+        }
+        base = g_static_ptr[dev];
     }
-    SAPS_HIP(c, hipGetLastError());
-    return SAPS_OK;
+
+    // a context on the stack that points into the scratch; nothing is allocated and nothing outlives the call
+    saps_ctx t;
+    t.n = n; t.N = N; t.ld = ld; t.msg_ld = msg_ld;
+    t.stream = (hipStream_t)hip_stream;
+    t.device = dev;
+    t.ntiles = (uint32_t)((N + TILE - 1) / TILE);
+    t.ngroups = (t.ntiles + GROUP - 1) / GROUP;
+    t.n_seg = 1;
+    t.T0 = (uint64_t)std::floor(4294967296.0 / c_ratio);
+    t.density = (double)t.T0 / 4294967296.0;
+    t.d_K = reinterpret_cast<int64_t*>(base + ST_OFF_K);
+    t.d_flag = reinterpret_cast<int32_t*>(base + ST_OFF_FLAG);
+    t.d_tile = reinterpret_cast<uint32_t*>(base + ST_OFF_TILE);
+    t.d_grp = reinterpret_cast<uint32_t*>(base + ST_OFF_GRP);
+    t.d_idx = reinterpret_cast<uint32_t*>(base + ST_OFF_IDX);
+    const saps_status st = round_impl(&t, X, G, V, lr, mu, seed, round, peer, idx, msg, K_dev, 0u);
+    if (st != SAPS_OK) g_static_err = t.err;
+    return st;
 }
 
 saps_status saps_consensus(saps_ctx* c, const float* X, float* mean_out, double* D_dev) {

@@ -57,7 +57,18 @@ def test_host_side_errors_without_a_gpu():
     L.saps_destroy.restype = ctypes.c_int
     assert L.saps_destroy(None) == 1
     L.saps_last_error.restype = ctypes.c_char_p
-    assert L.saps_last_error(None) == b"null context"
+    assert L.saps_last_error(None) == b""                   # no context: the thread's last context-free error, none yet
+    # the context-free entry point checks its limits before any HIP call
+    i32, i64, f32, u64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_float, ctypes.c_uint64, ctypes.c_void_p
+    L.saps_round_static.argtypes = [i32, i64, i64, ctypes.c_double, i64, vp, vp, vp, vp, f32, f32, u64, u64, vp, vp, vp, vp]
+    L.saps_round_static.restype = ctypes.c_int
+    peer = (ctypes.c_int32 * 2)(1, 0)
+    K = ctypes.c_int64(0)
+    big = (1 << 26) + 4
+    assert L.saps_round_static(2, big, big, 100.0, 64, None, None, None, None, 0.0, 0.0, 1, 1, peer, None, None, ctypes.byref(K)) == 1
+    assert b"67,108,864" in L.saps_last_error(None)
+    assert L.saps_round_static(2, 64, 64, 100.0, 64, None, None, None, None, 0.0, 0.0, 1, 1, peer, None, None, None) == 1
+    assert b"K_dev" in L.saps_last_error(None)
 
 
 def test_synthetic_workloads_have_the_stated_shapes():
