@@ -108,6 +108,11 @@ saps_status saps_round(saps_ctx* ctx, float* X, const float* G, float* V, float 
  * (bit-identical to saps_mask_compact; saps_merge; saps_sgd_step).  The packed messages then carry
  * the values before the step.  Without gradients (G == NULL) both orders coincide. */
 enum { SAPS_ROUND_MIX_THEN_STEP = 1u };
+/* Several local steps between exchanges (communication period tau > 1): a step without exchange is a
+ * round with W_t = I, for which Alg. 2 and Eq. (7) both reduce to the local step.  Per period call
+ * saps_sgd_step() tau - 1 times (fresh gradients each time), then saps_round() - or saps_round_ex() with
+ * SAPS_ROUND_MIX_THEN_STEP - with the gradients of the period's last step.  The momentum buffer V runs
+ * through local steps and rounds alike.  Only the exchanging call consumes a (seed, round) pair. */
 saps_status saps_round_ex(saps_ctx* ctx, float* X, const float* G, float* V, float lr, float mu,
                           uint64_t seed, uint64_t round, const int32_t* peer,
                           uint32_t* idx, float* msg, int64_t* K_dev, uint32_t flags);

@@ -153,6 +153,13 @@ saps_status make_units(saps_ctx* c, const int32_t* peer, Units* U, int32_t* n_un
         for (; k < MAX_INLINE_UNITS; ++k) U->packed[k] = 0u;
         return SAPS_OK;
     }
+    // The staging ring waits on an event and uploads from pinned memory: neither can be recorded into a
+    // graph (the copy would bake one stale staging slot into every replay).
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    SAPS_HIP(c, hipStreamIsCapturing(c->stream, &cap));
+    if (cap != hipStreamCaptureStatusNone)
+        return fail(c, SAPS_EINVAL, "the stream is capturing and the matching has more than 128 units: "
+                                    "only matchings that fit the kernel arguments can be captured in a graph");
     if (!c->ring[0].host) return fail(c, SAPS_EINVAL, "the matching has more than 128 units");
     Slot& s = c->ring[c->calls++ % RING];
     if (s.used) SAPS_HIP(c, hipEventSynchronize(s.done));

@@ -74,15 +74,18 @@ def test_cfg2_resnet20_n32_bandwidth_matching_50_rounds(B):
 
 
 def test_cfg3_resnet18_n32_fused_rounds(B):
+    # the benchmark run checks all 20 rounds of this workload bit for bit as well
     run_workload(B, "cfg3", 3)
 
 
-def test_cfg4_resnet50_n32_c1000(B):
-    run_workload(B, "cfg4", 2)
+def test_cfg4_resnet50_n32_c1000_all_20_rounds(B):
+    run_workload(B, "cfg4", 20, check_every=5)
 
 
-def test_cfg5_resnet18_n128_mixed_ratios(B):
-    run_workload(B, "cfg5", 1)
+def test_cfg5_resnet18_n128_mixed_ratios_all_10_rounds(B):
+    # the whole stated trajectory: from round 2 on the matchings come from Alg. 3 with a filled timestamp
+    # matrix (recently-connected graph, window expiry, second matching pass), at n = 128
+    run_workload(B, "cfg5", 10, check_every=5)
 
 
 def test_mnist_cnn_size_plain_sgd_rounds(B):

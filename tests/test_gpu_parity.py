@@ -429,6 +429,40 @@ def test_mix_then_step_round(B, n, N, ld, c, with_v):
             assert_bits(V.cpu().numpy(), Vo, f"V fused={fused}")
 
 
+@pytest.mark.parametrize("mix_first", [False, True], ids=["alg2_order", "recursion_order"])
+@pytest.mark.parametrize("with_v", [True, False])
+def test_tau_local_steps_between_exchanges(B, mix_first, with_v):
+    # communication period tau = 3 over two periods: (tau - 1) x saps_sgd_step, then one saps_round(_ex)
+    # with fresh gradients every step; the momentum buffer runs through local steps and rounds alike
+    n, N, ld, c, tau, periods = 6, 70_003, 70_016, 20.0, 3, 2
+    msg_ld = 4400
+    X0 = rand_models(n, N, ld, 1); V0 = rand_models(n, N, ld, 3, pad=333.0, scale=1e-3) if with_v else None
+    mu = 0.9 if with_v else 0.0
+    Gs = [rand_models(n, N, ld, 50 + k, pad=555.0, scale=1e-3) for k in range(tau * periods)]
+    peers = [rand_peer(n, 70 + r, singles=2 if r == 1 else 0) for r in range(periods)]
+    Xo = X0.copy(); Vo = None if V0 is None else V0.copy()
+    X = dev(X0); V = None if V0 is None else dev(V0)
+    idx = torch.full((msg_ld,), -1, dtype=torch.int32, device="cuda")
+    msg = torch.full((n, msg_ld), -5.0, device="cuda"); Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+    with B.SapsContext(n, N, ld, msg_ld, c) as ctx:
+        for r in range(periods):
+            for k in range(tau - 1):
+                G0 = Gs[r * tau + k]
+                assert O.sgd_step(Xo, G0, Vo, 0.1, mu, N=N) == O.OK
+                ctx.saps_sgd_step(X, dev(G0), V, 0.1, mu)
+            G0 = Gs[r * tau + tau - 1]
+            rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.1, mu, 8, r + 1, peers[r], c, msg_ld=msg_ld, mix_first=mix_first)
+            assert rc == O.OK
+            ctx.saps_round_ex(X, dev(G0), V, 0.1, mu, 8, r + 1, peers[r], idx, msg, Kd,
+                              flags=B.ROUND_MIX_THEN_STEP if mix_first else 0)
+            assert ctx.saps_poll_status() == (0, K)
+            assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K])
+            assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], f"msg period {r}")
+            assert_bits(X.cpu().numpy(), Xo, f"X period {r}")
+            if with_v:
+                assert_bits(V.cpu().numpy(), Vo, f"V period {r}")
+
+
 def test_round_ex_rejects_unknown_flags_and_flag0_is_saps_round(B):
     n, N, ld = 4, 6000, 6016
     X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2, scale=1e-3); peer = rand_peer(n, 1)
@@ -609,6 +643,36 @@ def test_round_loop_captured_in_a_graph_replays_like_eager(B, fused):
                 assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
                                    b.view(torch.int32) if b.dtype == torch.float32 else b), f"replay {rep}"
         assert ctx.saps_poll_status()[0] == 0
+
+
+def test_long_matching_is_refused_while_the_stream_is_capturing(B):
+    # more than 128 units go through a pinned staging slot (an event wait and a copy), which a graph cannot
+    # record faithfully: the call must say so instead of invalidating the capture or baking in a stale slot
+    n, N, ld, cap = 300, 257, 320, 260
+    peer = rand_peer(n, 3)                                        # 150 pairs > 128 units
+    s = torch.cuda.Stream()
+    with torch.cuda.stream(s):
+        X0 = dev(rand_models(n, N, ld, 1)); X = X0.clone()
+        msg = torch.zeros((n, cap), device="cuda"); idx = torch.zeros(cap, dtype=torch.int32, device="cuda")
+        Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+    s.synchronize()
+    with B.SapsContext(n, N, ld, cap, 2.0, stream=s) as ctx:
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=s):
+            X.add_(0.0)                                           # something to record
+            rc_round = ctx.saps_round(X, None, None, 0.0, 0.0, 1, 1, peer, idx, msg, Kd, check=False)
+            text = ctx._L.saps_last_error(ctx._h).decode()
+            rc_merge = ctx.saps_merge(X, peer, idx, msg, Kd, check=False)
+        assert rc_round == B.EINVAL and rc_merge == B.EINVAL and "capturing" in text
+        g.replay(); torch.cuda.synchronize()
+        assert torch.equal(X, X0)                                 # nothing of the round was recorded
+        # outside a capture the same call works and matches the oracle
+        ctx.saps_round(X, None, None, 0.0, 0.0, 1, 1, peer, idx, msg, Kd)
+        assert ctx.saps_poll_status()[0] == 0
+    Xo = X0.cpu().numpy().copy()
+    rc, K, idx_o, msg_o = O.round_(Xo, None, None, N, 0.0, 0.0, 1, 1, peer, 2.0, msg_ld=cap)
+    assert rc == O.OK and int(Kd.item()) == K
+    assert_bits(X.cpu().numpy(), Xo, "X")
 
 
 # ------------------------------------------------------------- optional outputs, lifetime
