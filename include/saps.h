@@ -14,6 +14,10 @@
  *                   coordinates of two matched workers become the mean of the two,
  *                   all other coordinates keep their value (Eq. (7))
  *
+ * Entry points of the method: saps_sgd_step, saps_mask_compact, saps_merge, saps_round (saps_round_ex,
+ * saps_round_static are variants of the last), saps_consensus.  Everything after saps_last_error() in this
+ * header (tuning knobs, event brackets, the two bandwidth yardsticks) is measurement tooling.
+ *
  * The mask is never stored.  Coordinate j of round t is kept iff
  *     Philox4x32-10(key = (lo32 seed, hi32 seed),
  *                   ctr = (lo32(j>>2), hi32(j>>2), lo32 t, hi32 t))[j & 3]  <  floor(2^32 / c_s)
@@ -166,7 +170,7 @@ enum {
 saps_status saps_set_tuning(saps_ctx* ctx, int32_t knob, int32_t value);
 
 /* Per-kernel timing for benchmarks.  saps_profile_enable(ctx, 1) makes every following
- * saps_round / saps_sgd_step / saps_consensus / saps_stream_copy bracket its dominant kernel (the fused
+ * saps_round / saps_sgd_step / saps_consensus / saps_stream_copy / saps_list_probe bracket its dominant kernel (the fused
  * round kernel, the list exchange kernel, the update kernel, the consensus kernel, the copy kernel) with a pair of
  * HIP events on the context's stream (at most 4096 pairs are kept; later launches are not
  * recorded).  saps_profile_read waits for the stream, returns the number of recorded
@@ -178,6 +182,14 @@ saps_status saps_profile_read(saps_ctx* ctx, int32_t* launches, double* total_ms
  * with the same access shape as the round kernels: the bandwidth yardstick of the
  * benchmark and the scale reference for profiler byte counters.  Not part of the method. */
 saps_status saps_stream_copy(saps_ctx* ctx, float* dst, const float* src, int64_t count);
+
+/* Yardstick of the index-list kernels, the counterpart of saps_stream_copy() for isolated accesses: every
+ * one of the n rows reads the 4-byte word at each of the coordinates idx[0..*K_dev) (as written by
+ * saps_mask_compact / saps_round); with write_back != 0 the same bits are stored back in place with the
+ * store policy the exchange uses for this layout, so X is unchanged either way.  No averaging and no
+ * messages: the time of this call is what the memory system needs for the exchange's access pattern.
+ * Entries >= N are skipped; *K_dev > msg_ld does nothing.  Not part of the method. */
+saps_status saps_list_probe(saps_ctx* ctx, float* X, const uint32_t* idx, const int64_t* K_dev, int32_t write_back);
 
 /* Library ABI version (bumped when a signature changes). */
 int32_t saps_abi_version(void);

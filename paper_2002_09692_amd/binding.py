@@ -22,7 +22,8 @@ _NAMES = {OK: "SAPS_OK", EINVAL: "SAPS_EINVAL", EMATCH: "SAPS_EMATCH", ECAPACITY
 
 EXPORTS = ("saps_abi_version", "saps_create", "saps_destroy", "saps_sgd_step", "saps_mask_compact", "saps_merge",
            "saps_round", "saps_poll_status", "saps_last_error", "saps_set_tuning", "saps_stream_copy",
-           "saps_profile_enable", "saps_profile_read", "saps_consensus", "saps_round_ex", "saps_round_static")
+           "saps_profile_enable", "saps_profile_read", "saps_consensus", "saps_round_ex", "saps_round_static",
+           "saps_list_probe")
 
 
 class SapsError(RuntimeError):
@@ -64,6 +65,7 @@ def load_library() -> C.CDLL:
     L.saps_consensus.argtypes = [vp, vp, vp, vp]; L.saps_consensus.restype = C.c_int
     L.saps_round_static.argtypes = [i32, i64, i64, C.c_double, i64, vp, vp, vp, vp, f32, f32, u64, u64, vp, vp, vp, vp]
     L.saps_round_static.restype = C.c_int
+    L.saps_list_probe.argtypes = [vp, vp, vp, vp, i32]; L.saps_list_probe.restype = C.c_int
     L.saps_profile_enable.argtypes = [vp, i32]; L.saps_profile_enable.restype = C.c_int
     L.saps_profile_read.argtypes = [vp, C.POINTER(i32), C.POINTER(C.c_double)]; L.saps_profile_read.restype = C.c_int
     _lib = L
@@ -263,6 +265,10 @@ class SapsContext:
     def saps_stream_copy(self, dst: torch.Tensor, src: torch.Tensor, check: bool = True) -> int:
         return self._rc(self._L.saps_stream_copy(self._h, _dev(dst, torch.float32, "dst"), _dev(src, torch.float32, "src"),
                                                  src.numel()), check)
+
+    def saps_list_probe(self, X, idx, K_dev, write_back: bool, check: bool = True) -> int:
+        return self._rc(self._L.saps_list_probe(self._h, self._rows(X, "X"), self._idx(idx), self._K(K_dev),
+                                                int(write_back)), check)
 
     def saps_profile_enable(self, on: bool) -> int:
         return self._rc(self._L.saps_profile_enable(self._h, int(on)), True)

@@ -62,6 +62,7 @@ struct saps_ctx {
     int32_t n_seg = 1;
     uint64_t T0 = 0;
     double density = 0.0;               // expected K / N
+    bool stream_scatter = true;         // scattered averages: streaming stores (true) or write-back stores (false)
     uint32_t* d_seg_end = nullptr;
     uint64_t* d_seg_T = nullptr;
     uint32_t* d_grp_seg = nullptr;      // first segment intersecting each group of 16 tiles
@@ -175,7 +176,12 @@ saps_status make_units(saps_ctx* c, const int32_t* peer, Units* U, int32_t* n_un
     return SAPS_OK;
 }
 
-uint32_t tile_blocks(const saps_ctx* c);
+void launch_idx_scatter(saps_ctx* c, const MaskParams& P, const Bases& Bp, uint32_t* list);
+
+// Scattered 4-byte stores of the list kernels: write-back stores while the 128-byte lines that one round
+// touches in all n rows fit the L2 caches (8 x 4 MB), streaming stores beyond.
+constexpr double SCATTER_WRITEBACK_MAX_BYTES = 32e6;
+bool stream_scatter_for(int32_t n, double expected_lines) { return (double)n * expected_lines * 128.0 > SCATTER_WRITEBACK_MAX_BYTES; }
 
 // The fused round kernel runs fastest with few resident waves per compute unit (fewer DRAM
 // pages open at once: measured best at 12 waves).  Residency is capped by giving each
@@ -223,7 +229,16 @@ saps_status enqueue_count_scan(saps_ctx* c, const MaskParams& P, int64_t* K_user
     return SAPS_OK;
 }
 
-uint32_t tile_blocks(const saps_ctx* c) { return (c->ntiles + WAVES - 1) / WAVES; }
+// K3 with one wave per tile, or one wave per group of 16 tiles when most tiles keep nothing
+// (fewer than half a coordinate expected per tile of 256).
+void launch_idx_scatter(saps_ctx* c, const MaskParams& P, const Bases& Bp, uint32_t* list) {
+    if (c->density * TILE < 0.5) {
+        const uint32_t waves = c->ngroups;
+        hipLaunchKernelGGL(idx_scatter_kernel<GROUP>, dim3((waves + WAVES - 1) / WAVES), dim3(BLOCK), 0, c->stream, P, c->ntiles, Bp, list);
+    } else {
+        hipLaunchKernelGGL(idx_scatter_kernel<1>, dim3((c->ntiles + WAVES - 1) / WAVES), dim3(BLOCK), 0, c->stream, P, c->ntiles, Bp, list);
+    }
+}
 
 uint32_t list_grid_x(const saps_ctx* c) {
     const int64_t b = (c->msg_ld + BLOCK - 1) / BLOCK;
@@ -307,10 +322,14 @@ saps_status round_impl(saps_ctx* c, float* X, const float* G, float* V, float lr
         profile_mark(c, true);
     } else {
         uint32_t* list = idx ? idx : c->d_idx;        // sparse masks: go through the index list
-        hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, Bp, list);
+        launch_idx_scatter(c, P, Bp, list);
         profile_mark(c, false);
-        hipLaunchKernelGGL(exchange_list_kernel, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
-                           X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);
+        if (c->stream_scatter)
+            hipLaunchKernelGGL(exchange_list_kernel<true>, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
+                               X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);
+        else
+            hipLaunchKernelGGL(exchange_list_kernel<false>, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
+                               X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);
         profile_mark(c, true);
     }
     SAPS_HIP(c, hipGetLastError());
@@ -321,7 +340,7 @@ saps_status round_impl(saps_ctx* c, float* X, const float* G, float* V, float lr
 
 extern "C" {
 
-int32_t saps_abi_version(void) { return 3; }
+int32_t saps_abi_version(void) { return 4; }
 
 // ctx == NULL: the calling thread's last saps_round_static() error
 const char* saps_last_error(const saps_ctx* ctx) { return ctx ? ctx->err.c_str() : g_static_err.c_str(); }
@@ -336,7 +355,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
     if (L->seg_off[0] != 0 || L->seg_off[L->n_seg] != L->N) return SAPS_EINVAL;
     std::vector<uint32_t> seg_end;
     std::vector<uint64_t> seg_T;
-    double expK = 0.0;
+    double expK = 0.0, expLines = 0.0;       // expected kept coordinates and touched 128-byte lines per row
     for (int32_t s = 0; s < L->n_seg; ++s) {
         const int64_t a = L->seg_off[s], b = L->seg_off[s + 1];
         const double cs = L->seg_c[s];
@@ -344,6 +363,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
         if (b == a) continue;
         const uint64_t T = (uint64_t)std::floor(4294967296.0 / cs);
         expK += (double)(b - a) * ((double)T / 4294967296.0);
+        expLines += (double)(b - a) / 32.0 * (1.0 - std::pow(1.0 - (double)T / 4294967296.0, 32.0));
         if (!seg_T.empty() && seg_T.back() == T) seg_end.back() = (uint32_t)b;
         else { seg_end.push_back((uint32_t)b); seg_T.push_back(T); }
     }
@@ -359,6 +379,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
     c->n_seg = (int32_t)seg_T.size();
     c->T0 = seg_T[0];
     c->density = L->N > 0 ? expK / (double)L->N : 0.0;
+    c->stream_scatter = stream_scatter_for(c->n, expLines);
 
     hipError_t e = hipSuccess;
     auto chk = [&](hipError_t r) { if (e == hipSuccess && r != hipSuccess) e = r; };
@@ -471,7 +492,7 @@ saps_status saps_mask_compact(saps_ctx* c, const float* X, uint64_t seed, uint64
     saps_status s = enqueue_count_scan(c, P, K_dev, &Bp);
     if (s) return s;
     if (c->ntiles == 0) return SAPS_OK;
-    hipLaunchKernelGGL(idx_scatter_kernel, dim3(tile_blocks(c)), dim3(BLOCK), 0, c->stream, P, c->ntiles, Bp, idx);
+    launch_idx_scatter(c, P, Bp, idx);
     hipLaunchKernelGGL(compact_values_kernel, dim3(list_grid_x(c), (uint32_t)c->n), dim3(BLOCK), 0, c->stream,
                        X, c->ld, idx, c->d_K, c->msg_ld, msg, c->msg_ld);
     SAPS_HIP(c, hipGetLastError());
@@ -491,8 +512,12 @@ saps_status saps_merge(saps_ctx* c, float* X, const int32_t* peer, const uint32_
     saps_status s = make_units(c, peer, &U, &n_units);
     if (s) return s;
     if (c->N == 0) return SAPS_OK;
-    hipLaunchKernelGGL(merge_kernel, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
-                       X, c->ld, U, idx, msg, c->msg_ld, K_dev, c->msg_ld);
+    if (c->stream_scatter)
+        hipLaunchKernelGGL(merge_kernel<true>, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
+                           X, c->ld, U, idx, msg, c->msg_ld, K_dev, c->msg_ld);
+    else
+        hipLaunchKernelGGL(merge_kernel<false>, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
+                           X, c->ld, U, idx, msg, c->msg_ld, K_dev, c->msg_ld);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;
 }
@@ -554,6 +579,7 @@ saps_status saps_round_static(int32_t n, int64_t N, int64_t ld, double c_ratio, 
     t.n_seg = 1;
     t.T0 = (uint64_t)std::floor(4294967296.0 / c_ratio);
     t.density = (double)t.T0 / 4294967296.0;
+    t.stream_scatter = stream_scatter_for(n, (double)N / 32.0 * (1.0 - std::pow(1.0 - t.density, 32.0)));
     t.d_K = reinterpret_cast<int64_t*>(base + ST_OFF_K);
     t.d_flag = reinterpret_cast<int32_t*>(base + ST_OFF_FLAG);
     t.d_tile = reinterpret_cast<uint32_t*>(base + ST_OFF_TILE);
@@ -626,6 +652,26 @@ saps_status saps_stream_copy(saps_ctx* c, float* dst, const float* src, int64_t 
     profile_mark(c, false);
     if (c->nontemporal) hipLaunchKernelGGL(stream_copy_kernel<true>, dim3((uint32_t)blocks), dim3(BLOCK), 0, c->stream, dst, src, c4);
     else hipLaunchKernelGGL(stream_copy_kernel<false>, dim3((uint32_t)blocks), dim3(BLOCK), 0, c->stream, dst, src, c4);
+    profile_mark(c, true);
+    SAPS_HIP(c, hipGetLastError());
+    return SAPS_OK;
+}
+
+saps_status saps_list_probe(saps_ctx* c, float* X, const uint32_t* idx, const int64_t* K_dev, int32_t write_back) {
+    if (!c) return SAPS_EINVAL;
+    if (saps_status ds = check_device(c)) return ds;
+    if (!X || !idx || !K_dev || !aligned16(X) || !aligned16(idx) || (reinterpret_cast<uintptr_t>(K_dev) & 7u))
+        return fail(c, SAPS_EINVAL, "X/idx/K null or misaligned");
+    if (c->N == 0) return SAPS_OK;
+    const dim3 grid(list_grid_x(c), (uint32_t)c->n);
+    uint32_t* sink = reinterpret_cast<uint32_t*>(c->d_partial);
+    profile_mark(c, false);
+    if (!write_back)
+        hipLaunchKernelGGL((list_probe_kernel<false, false>), grid, dim3(BLOCK), 0, c->stream, X, c->ld, idx, K_dev, c->msg_ld, (uint32_t)c->N, sink);
+    else if (c->stream_scatter)
+        hipLaunchKernelGGL((list_probe_kernel<true, true>), grid, dim3(BLOCK), 0, c->stream, X, c->ld, idx, K_dev, c->msg_ld, (uint32_t)c->N, sink);
+    else
+        hipLaunchKernelGGL((list_probe_kernel<true, false>), grid, dim3(BLOCK), 0, c->stream, X, c->ld, idx, K_dev, c->msg_ld, (uint32_t)c->N, sink);
     profile_mark(c, true);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;

@@ -219,14 +219,12 @@ struct Bases {
 };
 constexpr uint32_t DIRECT_MAX_GROUPS = 256;
 
-// Packed position of the first kept coordinate of a tile (its group's base plus the counts of
-// the tiles in front of it inside the group, at most 15 words, one per lane, summed by swaps)
-// and the round's K.  Wave-uniform; every lane of the wave must call it.
-__device__ __forceinline__ uint32_t tile_base_and_K(const Bases& Bp, uint32_t tile, bool first_wave, int64_t& K) {
-    const uint32_t g = tile / GROUP, r = tile % GROUP, lane = threadIdx.x & 63u;
-    uint32_t v = (lane < r) ? Bp.tile_cnt[g * GROUP + lane] : 0u;
-    uint32_t before = 0u, all = 0u;
+// Packed position of the first kept coordinate of group g and the round's K.  Wave-uniform; every
+// lane of the wave must call it.
+__device__ __forceinline__ uint32_t group_base_and_K(const Bases& Bp, uint32_t g, bool first_wave, int64_t& K) {
     if (Bp.direct) {
+        const uint32_t lane = threadIdx.x & 63u;
+        uint32_t before = 0u, all = 0u;
 #pragma unroll
         for (uint32_t k = 0; k < DIRECT_MAX_GROUPS / 64u; ++k) {
             const uint32_t gi = lane + 64u * k;
@@ -234,10 +232,6 @@ __device__ __forceinline__ uint32_t tile_base_and_K(const Bases& Bp, uint32_t ti
             all += c;
             before += (gi < g) ? c : 0u;
         }
-    }
-#pragma unroll
-    for (int d = 1; d < GROUP; d <<= 1) v += __shfl_xor(v, d, 64);
-    if (Bp.direct) {
 #pragma unroll
         for (int d = 1; d < 64; d <<= 1) { before += __shfl_xor(before, d, 64); all += __shfl_xor(all, d, 64); }
         K = (int64_t)all;
@@ -246,31 +240,67 @@ __device__ __forceinline__ uint32_t tile_base_and_K(const Bases& Bp, uint32_t ti
             if (Bp.K_user) *Bp.K_user = K;
             if (K > Bp.cap) *Bp.flag = 1;
         }
-        return __builtin_amdgcn_readfirstlane(before) + __builtin_amdgcn_readfirstlane(v);
+        return __builtin_amdgcn_readfirstlane(before);
     }
     K = *Bp.K_int;
-    return Bp.grp[g] + __builtin_amdgcn_readfirstlane(v);
+    return Bp.grp[g];
+}
+
+// Packed position of the first kept coordinate of a tile (its group's base plus the counts of
+// the tiles in front of it inside the group, at most 15 words, one per lane, summed by swaps)
+// and the round's K.  Wave-uniform; every lane of the wave must call it.
+__device__ __forceinline__ uint32_t tile_base_and_K(const Bases& Bp, uint32_t tile, bool first_wave, int64_t& K) {
+    const uint32_t g = tile / GROUP, r = tile % GROUP, lane = threadIdx.x & 63u;
+    uint32_t v = (lane < r) ? Bp.tile_cnt[g * GROUP + lane] : 0u;
+    const uint32_t gbase = group_base_and_K(Bp, g, first_wave, K);
+#pragma unroll
+    for (int d = 1; d < GROUP; d <<= 1) v += __shfl_xor(v, d, 64);
+    return gbase + __builtin_amdgcn_readfirstlane(v);
 }
 
 // --------------------------------------------------------- K3: ascending index list idx
+// A wave owns TPW consecutive tiles of one group of 16.  The group's tile counts arrive with one load
+// (together with the group base and K), then only the tiles that keep something are visited.  TPW = 1
+// gives every tile its own wave (dense masks: the Philox blocks are the work); TPW = 16 lets one wave
+// step over a whole group when most tiles keep nothing (at c = 1000 three quarters of them), so that the
+// memory latency is paid once per group and not once per tile.
+template <int TPW>
 __global__ __launch_bounds__(BLOCK) void idx_scatter_kernel(MaskParams P, uint32_t ntiles, Bases Bp,
                                                             uint32_t* __restrict__ idx) {
-    const uint32_t tile = blockIdx.x * WAVES + (threadIdx.x >> 6);
-    if (tile >= ntiles) return;
-    const bool first_wave = (tile == 0u);
-    if (!first_wave && Bp.tile_cnt[tile] == 0u) return;  // nothing kept here: no need to redo the Philox block
+    static_assert(TPW == 1 || TPW == 2 || TPW == 4 || TPW == 8 || TPW == 16, "TPW divides the group");
+    const uint32_t w = blockIdx.x * WAVES + (threadIdx.x >> 6);      // wave-uniform
+    const uint32_t tfirst = w * (uint32_t)TPW;                       // first tile of this wave
+    if (tfirst >= ntiles) return;
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t g = tfirst / GROUP, t0 = g * GROUP;
+    const uint32_t cnt = (lane < (uint32_t)GROUP && t0 + lane < ntiles) ? Bp.tile_cnt[t0 + lane] : 0u;
     int64_t K;
-    const uint32_t base = tile_base_and_K(Bp, tile, first_wave, K);
+    const uint32_t gbase = group_base_and_K(Bp, g, w == 0u, K);
     if (K > Bp.cap) return;
-    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
-    const uint32_t q = tile * 64u + (threadIdx.x & 63u);
-    const uint32_t m = mask4(P, tile, threadIdx.x & 63u, seg0);
-    uint32_t total;
-    uint32_t pos = base + wave_prefix(m, total);
-    if (m) {
+    uint32_t inc = cnt;                                              // inclusive prefix over the group's 16 tiles
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
-            if ((m >> r) & 1u) idx[pos++] = (q << 2) + r;
+    for (int d = 1; d < GROUP; d <<= 1) {
+        const uint32_t o = __shfl_up(inc, d, 64);
+        if ((int)lane >= d) inc += o;
+    }
+    const uint32_t excl = inc - cnt;
+    const uint32_t r0 = tfirst - t0;
+    uint64_t todo = __ballot(cnt != 0u) & ((TPW == 16) ? 0xFFFFull : (((1ull << TPW) - 1ull) << r0));
+    while (todo) {
+        const int r = __builtin_ctzll(todo);
+        todo &= todo - 1;
+        const uint32_t tile = t0 + (uint32_t)r;
+        const uint32_t tbase = gbase + (uint32_t)__shfl((int)excl, r, 64);
+        const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
+        const uint32_t q = tile * 64u + lane;
+        const uint32_t m = mask4(P, tile, lane, seg0);
+        uint32_t total;
+        uint32_t pos = tbase + wave_prefix(m, total);
+        if (m) {
+#pragma unroll
+            for (int k = 0; k < 4; ++k)
+                if ((m >> k) & 1u) idx[pos++] = (q << 2) + k;
+        }
     }
 }
 
@@ -300,6 +330,13 @@ template <bool NT> __device__ __forceinline__ void st4(float* p, f4 v) {
 // (0.57 with "nt" alone); gathers stay plain, a non-temporal hint on them measured slower (0.74 ms).
 __device__ __forceinline__ void st1(float* p, float v) {
     asm volatile("global_store_dword %0, %1, off sc1 nt\n\ts_nop 1" : : "v"(p), "v"(v) : "memory");
+}
+// Scattered 4-byte store of an averaged value: streaming (sc1 nt) in general, plain write-back
+// (STREAM = false) when the lines that a round touches in all rows fit the L2 caches (32 x 272 k at
+// c = 100: 4.2 instead of 6.6 us).  On models that do not fit, write-back stores measured slower
+// (32 x 25.6 M at c = 1000: 45 against 42 us; 128 x 11.2 M mixed ratios: 0.61 against 0.52 ms).
+template <bool STREAM> __device__ __forceinline__ void st1x(float* p, float v) {
+    if (STREAM) st1(p, v); else *p = v;
 }
 
 // Local step on one value (Alg. 2 line 5 with momentum): two correctly rounded FMAs.
@@ -351,6 +388,7 @@ __global__ __launch_bounds__(BLOCK) void compact_values_kernel(const float* __re
 }
 
 // -------------------------------------------------- K6: average the two packed messages
+template <bool STREAM>
 __global__ __launch_bounds__(BLOCK) void merge_kernel(float* __restrict__ X, int64_t ld, Units U,
                                                       const uint32_t* __restrict__ idx, const float* __restrict__ msg,
                                                       int64_t msg_ld, const int64_t* __restrict__ K_dev, int64_t cap) {
@@ -366,13 +404,15 @@ __global__ __launch_bounds__(BLOCK) void merge_kernel(float* __restrict__ X, int
     for (int64_t k = (int64_t)blockIdx.x * BLOCK + threadIdx.x; k < K; k += (int64_t)gridDim.x * BLOCK) {
         const float avg = (a[k] + b[k]) * 0.5f;
         const uint32_t j = idx[k];
-        st1(xi + j, avg);
-        st1(xp + j, avg);
+        st1x<STREAM>(xi + j, avg);
+        st1x<STREAM>(xp + j, avg);
     }
 }
 
 // -------------------------- K8: exchange-only round through the index list (sparse masks)
-// unit u = (i, p): a matched pair with i < p, or an unmatched worker with i == p.
+// unit u = (i, p): a matched pair with i < p, or an unmatched worker with i == p.  Both gathers are
+// requested before anything is stored.
+template <bool STREAM>
 __global__ __launch_bounds__(BLOCK) void exchange_list_kernel(float* __restrict__ X, int64_t ld, Units U,
                                                               const uint32_t* __restrict__ idx,
                                                               const int64_t* __restrict__ K_int, int64_t cap,
@@ -386,13 +426,15 @@ __global__ __launch_bounds__(BLOCK) void exchange_list_kernel(float* __restrict_
     for (int64_t k = (int64_t)blockIdx.x * BLOCK + threadIdx.x; k < K; k += (int64_t)gridDim.x * BLOCK) {
         const uint32_t j = idx[k];
         const float a = xi[j];
-        if (msg) st1(msg + (int64_t)i * msg_ld + k, a);
+        const float b = xp[j];                       // p == i: the same word again
+        if (msg) {
+            st1(msg + (int64_t)i * msg_ld + k, a);
+            if (p != i) st1(msg + (int64_t)p * msg_ld + k, b);
+        }
         if (p != i) {
-            const float b = xp[j];
-            if (msg) st1(msg + (int64_t)p * msg_ld + k, b);
             const float avg = (a + b) * 0.5f;
-            st1(xi + j, avg);
-            st1(xp + j, avg);
+            st1x<STREAM>(xi + j, avg);
+            st1x<STREAM>(xp + j, avg);
         }
     }
 }
@@ -671,6 +713,27 @@ __global__ __launch_bounds__(BLOCK) void stream_copy_kernel(float* __restrict__ 
                                                             int64_t count4) {
     const int64_t q = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
     if (q < count4) st4<NT>(dst + 4 * q, ld4<NT>(src + 4 * q));
+}
+
+// ------------------------------------------ yardstick of the list kernels (isolated accesses)
+// Every row reads the 4-byte word at each listed coordinate; with WRITE the same bits are stored back
+// in place with the store policy of the exchange (the matrix does not change).  No averaging, no messages:
+// what remains is what the memory system gives for the access pattern of the list exchange.
+template <bool WRITE, bool STREAM>
+__global__ __launch_bounds__(BLOCK) void list_probe_kernel(float* __restrict__ X, int64_t ld,
+                                                           const uint32_t* __restrict__ idx,
+                                                           const int64_t* __restrict__ K_dev, int64_t cap,
+                                                           uint32_t N, uint32_t* __restrict__ sink) {
+    const int64_t K = *K_dev;
+    if (K > cap || K < 0) return;
+    float* x = X + (int64_t)blockIdx.y * ld;
+    for (int64_t k = (int64_t)blockIdx.x * BLOCK + threadIdx.x; k < K; k += (int64_t)gridDim.x * BLOCK) {
+        const uint32_t j = idx[k];
+        if (j >= N) continue;                                       // a foreign list must not lead outside the row
+        const float v = x[j];
+        if (WRITE) st1x<STREAM>(x + j, v);
+        else if (__float_as_uint(v) == 0xFFFFFFFFu) *sink = 1u;     // keeps the load; a model never holds this pattern
+    }
 }
 
 }  // namespace saps

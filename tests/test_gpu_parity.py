@@ -711,3 +711,65 @@ def test_many_contexts_created_and_destroyed(B):
                 assert ctx.saps_poll_status()[0] == 0
     torch.cuda.synchronize()
     assert free0 - torch.cuda.mem_get_info()[0] < (64 << 20)          # contexts give their scratch back
+
+
+# ------------------------------------------------------------------------------ list yardstick
+@pytest.mark.parametrize("write_back", [False, True])
+def test_list_probe_leaves_the_models_unchanged(B, write_back):
+    n, N, ld = 6, 70_001, 70_016
+    X0 = rand_models(n, N, ld, 11)
+    cap = 2048
+    X = dev(X0)
+    idx = torch.full((cap,), -1, dtype=torch.int32, device="cuda")
+    msg = torch.zeros((n, cap), dtype=torch.float32, device="cuda")
+    Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+    with B.SapsContext(n, N, ld, cap, 100.0) as ctx:
+        ctx.saps_mask_compact(X, 3, 1, idx, msg, Kd)
+        ctx.saps_list_probe(X, idx, Kd, write_back)
+        # a foreign list with entries beyond N (and beyond ld) is skipped entry by entry
+        bad = torch.tensor([0, 5, N, N + 1, ld + 100, 0x7FFFFFF0, N - 1] + [1] * (cap - 7), dtype=torch.int64).to(torch.int32).cuda()
+        Kb = torch.tensor([7], dtype=torch.int64, device="cuda")
+        ctx.saps_list_probe(X, bad, Kb, write_back)
+        # K beyond the capacity: nothing happens
+        Kbig = torch.tensor([cap + 1], dtype=torch.int64, device="cuda")
+        ctx.saps_list_probe(X, idx, Kbig, write_back)
+        st, _ = ctx.saps_poll_status()
+    assert st == 0
+    assert_bits(X.cpu().numpy(), X0, "X after the probe")
+
+
+def test_list_exchange_store_policies_agree_with_the_oracle(B):
+    """The list exchange picks write-back or streaming stores from the size of the lines a round touches:
+    few rows take the first, many rows of a long model the second; both must give the oracle's bits."""
+    for n, N, c in ((4, 300_000, 50.0), (64, 2_500_000, 20.0)):       # 4 x 8 k lines (4 MB), 64 x 63 k lines (0.52 GB)
+        ld = (N + 63) // 64 * 64
+        cap = int(N / c * 1.2) // 4 * 4
+        r = run_round_both(B, n, N, ld, c, None, 9, 2, rand_peer(n, 5), fused=False, msg_ld=cap,
+                           tuning=((B.TUNE_EXCHANGE_PATH, 1),))
+        check_round(r, N)
+
+
+@pytest.mark.parametrize("N", [1, 255, 4097, 70_001, 1_048_577, 1_300_000])
+@pytest.mark.parametrize("c", [600.0, 1000.0, 20_000.0])
+def test_index_list_of_sparse_masks(B, N, c):
+    """Sparse masks take the index-list kernel in which one wave walks a whole group of 16 tiles: one group and
+    less, ragged last groups, models below and above the size where the scan launch is skipped."""
+    n = 2
+    ld = (N + 63) // 64 * 64
+    msg_ld = max(4, (int(N / c * 2) + 64) // 4 * 4)
+    X0 = rand_models(n, N, ld, 7)
+    for seed, rnd in ((1, 1), (2, 9)):
+        rc, K, idx_o, msg_o = O.mask_compact(X0, N, seed, rnd, c, msg_ld=msg_ld)
+        assert rc == O.OK
+        X = dev(X0)
+        idx = torch.full((msg_ld,), -1, dtype=torch.int32, device="cuda")
+        msg = torch.full((n, msg_ld), -5.0, device="cuda")
+        Kd = torch.full((1,), -1, dtype=torch.int64, device="cuda")
+        with B.SapsContext(n, N, ld, msg_ld, c) as ctx:
+            ctx.saps_mask_compact(X, seed, rnd, idx, msg, Kd)
+            assert ctx.saps_poll_status() == (0, K)
+        assert int(Kd.item()) == K
+        got = idx.cpu().numpy().view(np.uint32)
+        assert np.array_equal(got[:K], idx_o[:K])
+        assert np.all(got[K:] == 0xFFFFFFFF), "idx written beyond K"
+        assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], "msg")
