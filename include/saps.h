@@ -164,7 +164,8 @@ enum {
     SAPS_TUNE_PAIRS_PER_BLOCK = 0, /* fused round: matched pairs handled per workgroup: 1, 2, 4, 8 */
     SAPS_TUNE_XCD_REMAP = 1,       /* fused round: 0 = tiles in launch order, 1 = contiguous tile range per XCD */
     SAPS_TUNE_NONTEMPORAL = 2,     /* fused round and local step: 0 = plain, 1 = non-temporal loads/stores */
-    SAPS_TUNE_EXCHANGE_PATH = 3,   /* exchange-only round: 0 = built-in choice by expected density, 1 = index list, 2 = tile walk */
+    SAPS_TUNE_EXCHANGE_PATH = 3,   /* exchange-only round: 0 = built-in choice by expected density, 1 = index list, 2 = tile walk,
+                                      3 = index list, but whole tiles that keep at least every 12th coordinate are streamed */
     SAPS_TUNE_BLOCKS_PER_CU = 4    /* fused round: resident 2-wave workgroups per compute unit, 3..16, 0 = no limit, -1 = built-in choice */
 };
 saps_status saps_set_tuning(saps_ctx* ctx, int32_t knob, int32_t value);

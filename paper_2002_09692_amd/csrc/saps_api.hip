@@ -66,6 +66,9 @@ struct saps_ctx {
     uint32_t* d_seg_end = nullptr;
     uint64_t* d_seg_T = nullptr;
     uint32_t* d_grp_seg = nullptr;      // first segment intersecting each group of 16 tiles
+    uint32_t* d_walk_tiles = nullptr;   // whole tiles dense enough to be exchanged by streaming (hybrid path)
+    uint32_t* d_walk_bits = nullptr;    // the same set as one bit per tile
+    uint32_t n_walk = 0;
     // scratch
     uint32_t ngroups = 0;
     uint32_t* d_tile = nullptr;         // ntiles kept counts, one per wave tile
@@ -321,15 +324,30 @@ saps_status round_impl(saps_ctx* c, float* X, const float* G, float* V, float lr
         launch_fused<2>(c, P, A, U);                   // dense masks: walk the tiles
         profile_mark(c, true);
     } else {
-        uint32_t* list = idx ? idx : c->d_idx;        // sparse masks: go through the index list
+        // sparse masks: go through the index list; path 3 streams the dense tiles of a mixed layout instead
+        // (measured slower than the list alone on the 128 x 11.2 M mixed-ratio workload, so never the default)
+        const bool hybrid = c->exchange_path == 3 && c->n_walk > 0 && c->d_walk_tiles;
+        uint32_t* list = idx ? idx : c->d_idx;
         launch_idx_scatter(c, P, Bp, list);
         profile_mark(c, false);
-        if (c->stream_scatter)
-            hipLaunchKernelGGL(exchange_list_kernel<true>, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
-                               X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);
-        else
-            hipLaunchKernelGGL(exchange_list_kernel<false>, dim3(list_grid_x(c), (uint32_t)n_units), dim3(BLOCK), 0, c->stream,
-                               X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld);
+        if (hybrid) {
+            const int32_t upw = 2;
+            const dim3 wgrid((c->n_walk + FUSED_WAVES - 1) / FUSED_WAVES, (uint32_t)((n_units + upw - 1) / upw));
+            hipLaunchKernelGGL(walk_tiles_kernel<true>, wgrid, dim3(FUSED_BLOCK), 0, c->stream, P, Bp, X, c->ld, U, n_units, upw,
+                               c->d_walk_tiles, c->n_walk, msg, c->msg_ld);
+        }
+        const dim3 lgrid(list_grid_x(c), (uint32_t)n_units);
+        if (hybrid) {
+            if (c->stream_scatter)
+                hipLaunchKernelGGL((exchange_list_kernel<true, true>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits);
+            else
+                hipLaunchKernelGGL((exchange_list_kernel<false, true>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits);
+        } else {
+            if (c->stream_scatter)
+                hipLaunchKernelGGL((exchange_list_kernel<true, false>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits);
+            else
+                hipLaunchKernelGGL((exchange_list_kernel<false, false>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits);
+        }
         profile_mark(c, true);
     }
     SAPS_HIP(c, hipGetLastError());
@@ -396,6 +414,31 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
         }
     }
     chk(hipMalloc(&c->d_grp_seg, sizeof(uint32_t) * grp_seg.size()));
+    // dense tiles of the hybrid exchange: whole tiles that are expected to keep at least every 12th coordinate
+    std::vector<uint32_t> walk_tiles, walk_bits((size_t)c->ntiles / 32 + 1, 0u);
+    {
+        size_t si = 0;
+        for (uint32_t t = 0; t < c->ntiles; ++t) {
+            const uint64_t a = (uint64_t)t * TILE, b = a + TILE;
+            if (b > (uint64_t)L->N) break;
+            while (si + 1 < seg_end.size() && (uint64_t)seg_end[si] <= a) ++si;
+            double e = 0.0;
+            size_t s2 = si;
+            for (uint64_t x = a; x < b;) {
+                const uint64_t y = std::min<uint64_t>(b, seg_end[s2]);
+                e += (double)(y - x) * ((double)seg_T[s2] / 4294967296.0);
+                x = y;
+                if (x < b) ++s2;
+            }
+            if (e >= (double)TILE / 12.0) { walk_tiles.push_back(t); walk_bits[t >> 5] |= 1u << (t & 31u); }
+        }
+    }
+    c->n_walk = (uint32_t)walk_tiles.size();
+    chk(hipMalloc(&c->d_walk_tiles, sizeof(uint32_t) * (walk_tiles.size() + 1)));
+    chk(hipMalloc(&c->d_walk_bits, sizeof(uint32_t) * walk_bits.size()));
+    if (e == hipSuccess && !walk_tiles.empty())
+        chk(hipMemcpy(c->d_walk_tiles, walk_tiles.data(), sizeof(uint32_t) * walk_tiles.size(), hipMemcpyHostToDevice));
+    if (e == hipSuccess) chk(hipMemcpy(c->d_walk_bits, walk_bits.data(), sizeof(uint32_t) * walk_bits.size(), hipMemcpyHostToDevice));
     if (e == hipSuccess) chk(hipMemcpy(c->d_grp_seg, grp_seg.data(), sizeof(uint32_t) * grp_seg.size(), hipMemcpyHostToDevice));
     chk(hipMalloc(&c->d_tile, sizeof(uint32_t) * ((size_t)c->ntiles + 1)));
     chk(hipMalloc(&c->d_grp, sizeof(uint32_t) * ((size_t)c->ngroups + 1)));
@@ -424,7 +467,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
 saps_status saps_destroy(saps_ctx* c) {
     if (!c) return SAPS_EINVAL;
     (void)hipStreamSynchronize(c->stream);
-    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_grp_seg); (void)hipFree(c->d_tile); (void)hipFree(c->d_grp); (void)hipFree(c->d_K); (void)hipFree(c->d_partial);
+    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_grp_seg); (void)hipFree(c->d_walk_tiles); (void)hipFree(c->d_walk_bits); (void)hipFree(c->d_tile); (void)hipFree(c->d_grp); (void)hipFree(c->d_K); (void)hipFree(c->d_partial);
     (void)hipFree(c->d_flag); (void)hipFree(c->d_idx); (void)hipFree(c->d_match);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (int r = 0; r < RING; ++r) {
@@ -451,7 +494,7 @@ saps_status saps_set_tuning(saps_ctx* c, int32_t knob, int32_t value) {
             if (value != -1 && value != 0 && (value < 3 || value > 16)) return fail(c, SAPS_EINVAL, "blocks per CU");
             c->blocks_per_cu = value; return SAPS_OK;
         case SAPS_TUNE_EXCHANGE_PATH:
-            if (value < 0 || value > 2) return fail(c, SAPS_EINVAL, "exchange path");
+            if (value < 0 || value > 3) return fail(c, SAPS_EINVAL, "exchange path");
             c->exchange_path = value; return SAPS_OK;
         default: return fail(c, SAPS_EINVAL, "unknown knob");
     }

@@ -411,12 +411,14 @@ __global__ __launch_bounds__(BLOCK) void merge_kernel(float* __restrict__ X, int
 
 // -------------------------- K8: exchange-only round through the index list (sparse masks)
 // unit u = (i, p): a matched pair with i < p, or an unmatched worker with i == p.  Both gathers are
-// requested before anything is stored.
-template <bool STREAM>
+// requested before anything is stored.  With SKIP, coordinates inside the tiles marked in walk_bits
+// (one bit per tile) are left to the tile walk K8w.
+template <bool STREAM, bool SKIP>
 __global__ __launch_bounds__(BLOCK) void exchange_list_kernel(float* __restrict__ X, int64_t ld, Units U,
                                                               const uint32_t* __restrict__ idx,
                                                               const int64_t* __restrict__ K_int, int64_t cap,
-                                                              float* __restrict__ msg, int64_t msg_ld) {
+                                                              float* __restrict__ msg, int64_t msg_ld,
+                                                              const uint32_t* __restrict__ walk_bits) {
     const int64_t K = *K_int;
     if (K > cap) return;
     int32_t i, p;
@@ -425,6 +427,10 @@ __global__ __launch_bounds__(BLOCK) void exchange_list_kernel(float* __restrict_
     float* xp = X + (int64_t)p * ld;
     for (int64_t k = (int64_t)blockIdx.x * BLOCK + threadIdx.x; k < K; k += (int64_t)gridDim.x * BLOCK) {
         const uint32_t j = idx[k];
+        if (SKIP) {
+            const uint32_t t = j / (uint32_t)TILE;
+            if ((walk_bits[t >> 5] >> (t & 31u)) & 1u) continue;
+        }
         const float a = xi[j];
         const float b = xp[j];                       // p == i: the same word again
         if (msg) {
@@ -621,6 +627,68 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
         }
         finish_unit<MODE, NT, MIXFIRST>(A, cur, i, p, j0, nval, m, pos0);
         if (PPB > 1) { cur = nxt; i = in; p = pn; }
+    }
+}
+
+// ------------------------------- K8w: exchange-only round of the listed (dense) tiles by streaming
+// One wave per listed tile and chunk of units: the tile's 1 KB of both rows is read whole, the kept
+// coordinates are packed and averaged, and the tile is written back whole.  Where a mask keeps most
+// 128-byte lines anyway (c = 10: 97 %), whole-tile traffic costs no more bytes than touching the kept
+// words one by one and avoids partial writes.  Only whole tiles (all 256 coordinates below N) are listed.
+constexpr int WALK_UNITS_IN_FLIGHT = 2;
+
+template <bool NT>
+__global__ __launch_bounds__(FUSED_BLOCK) void walk_tiles_kernel(MaskParams P, Bases Bp, float* __restrict__ X, int64_t ld,
+                                                                 Units U, int32_t n_units, int32_t units_per_wave,
+                                                                 const uint32_t* __restrict__ walk_tiles, uint32_t n_walk,
+                                                                 float* __restrict__ msg, int64_t msg_ld) {
+    const uint32_t w = blockIdx.x * FUSED_WAVES + (threadIdx.x >> 6);
+    if (w >= n_walk) return;
+    const uint32_t tile = walk_tiles[w];
+    const uint32_t lane = threadIdx.x & 63u;
+    const uint32_t j0 = (tile * 64u + lane) << 2;
+    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
+    const uint32_t m = mask4(P, tile, lane, seg0);
+    uint32_t total;
+    int64_t K;
+    const uint32_t pos0 = tile_base_and_K(Bp, tile, false, K) + wave_prefix(m, total);
+    if (K > Bp.cap) return;
+    const int u_lo = blockIdx.y * units_per_wave, u_hi = min(u_lo + units_per_wave, n_units);
+    for (int u0 = u_lo; u0 < u_hi; u0 += WALK_UNITS_IN_FLIGHT) {
+        f4 a[WALK_UNITS_IN_FLIGHT], b[WALK_UNITS_IN_FLIGHT];
+        int32_t ii[WALK_UNITS_IN_FLIGHT], pp[WALK_UNITS_IN_FLIGHT];
+#pragma unroll
+        for (int r = 0; r < WALK_UNITS_IN_FLIGHT; ++r) {
+            if (u0 + r < u_hi) {
+                unit_at(U, u0 + r, ii[r], pp[r]);
+                a[r] = ld4<NT>(X + (int64_t)ii[r] * ld + j0);
+                b[r] = ld4<NT>(X + (int64_t)pp[r] * ld + j0);
+            }
+        }
+#pragma unroll
+        for (int r = 0; r < WALK_UNITS_IN_FLIGHT; ++r) {
+            if (u0 + r < u_hi) {
+                const int32_t i = ii[r], p = pp[r];
+                uint32_t pos = pos0;
+                f4 xa = a[r], xb = b[r];
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    if ((m >> q) & 1u) {
+                        if (msg) {
+                            msg[(int64_t)i * msg_ld + pos] = xa[q];
+                            if (p != i) msg[(int64_t)p * msg_ld + pos] = xb[q];
+                        }
+                        const float avg = (xa[q] + xb[q]) * 0.5f;
+                        xa[q] = avg; xb[q] = avg;
+                        ++pos;
+                    }
+                }
+                if (p != i) {
+                    st4<NT>(X + (int64_t)i * ld + j0, xa);
+                    st4<NT>(X + (int64_t)p * ld + j0, xb);
+                }
+            }
+        }
     }
 }
 

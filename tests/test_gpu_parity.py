@@ -185,14 +185,14 @@ def test_fused_round_without_optional_outputs(B):
 
 
 @pytest.mark.parametrize("n,N,ld,c", SHAPES)
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 def test_exchange_only_round_both_paths(B, n, N, ld, c, path):
     peer = rand_peer(n, n * 3 + N, singles=1 if n > 2 else 0)
     r = run_round_both(B, n, N, ld, c, None, 2**40 + 17, 2**35 + 1, peer, fused=False, tuning=[(B.TUNE_EXCHANGE_PATH, path)])
     check_round(r, N)
 
 
-@pytest.mark.parametrize("path", [1, 2])
+@pytest.mark.parametrize("path", [1, 2, 3])
 def test_exchange_only_without_optional_outputs(B, path):
     n, N, ld = 4, 30_000, 30_016
     r = run_round_both(B, n, N, ld, 50.0, None, 3, 3, rand_peer(n, 5), fused=False, outputs=False,
@@ -207,7 +207,7 @@ def test_per_segment_ratios_at_unaligned_offsets(B, fused):
     cs = [1.0, 2.0, 7.0, 100.0, 10.0, 1000.0]
     r = run_round_both(B, n, N, ld, cs, off, 9, 2, rand_peer(n, 4), fused=fused)
     check_round(r, N)
-    for path in (1, 2):
+    for path in (1, 2, 3):
         r = run_round_both(B, n, N, ld, cs, off, 9, 2, rand_peer(n, 4), fused=False, tuning=[(B.TUNE_EXCHANGE_PATH, path)])
         check_round(r, N)
 
@@ -298,7 +298,7 @@ def test_capacity_overflow_skips_the_round(B):
     X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2); V0 = rand_models(n, N, ld, 3)
     peer = rand_peer(n, 1)
     for fused in (True, False):
-        for path in (1, 2):
+        for path in (1, 2, 3):
             X, G, V = dev(X0), dev(G0), dev(V0)
             idx = torch.full((100,), -1, dtype=torch.int32, device="cuda"); msg = torch.full((n, 100), -5.0, device="cuda")
             Kd = torch.full((1,), -1, dtype=torch.int64, device="cuda")
@@ -361,7 +361,7 @@ def test_special_values_travel_through_merge(B):
     b = np.array([1.0, -inf, 1.0, 0.0, tiny, tiny, 3.4e38, -1.0], np.float32)
     X0 = np.stack([a, b]); Xo = X0.copy()
     O.round_(Xo, None, None, N, 0, 0, 0, 1, np.array([1, 0]), 1.0)
-    for path in (1, 2):
+    for path in (1, 2, 3):
         X = dev(X0)
         with B.SapsContext(n, N, ld, 8, 1.0) as ctx:
             ctx.saps_set_tuning(B.TUNE_EXCHANGE_PATH, path)
@@ -773,3 +773,20 @@ def test_index_list_of_sparse_masks(B, N, c):
         assert np.array_equal(got[:K], idx_o[:K])
         assert np.all(got[K:] == 0xFFFFFFFF), "idx written beyond K"
         assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], "msg")
+
+
+@pytest.mark.parametrize("n", [2, 5, 130])
+def test_hybrid_exchange_streams_dense_tiles_and_lists_the_rest(B, n):
+    """Exchange path 3: whole tiles that keep at least every 12th coordinate are streamed, everything else goes
+    through the index list; segment cuts inside tiles, ratios on both sides of the threshold, a dense last
+    tile that is not whole, unmatched workers, and runs without the optional outputs."""
+    rng = np.random.default_rng(n)
+    sizes = [700, 3000, 256, 1, 5000, 255, 2048, 10_000, 513, 4096, 77, 3000, 1500]
+    cs = [10.0, 100.0, 1.0, 4.0, 1000.0, 12.0, 13.0, 2.0, 100.0, 11.9, 3.0, 1000.0, 5.0]
+    off = synth.segment_offsets(sizes)
+    N = int(off[-1]); ld = (N + 63) // 64 * 64
+    peer = rand_peer(n, 7 * n + 1, singles=(1 if n % 2 else 2) if n > 3 else 0)
+    for outputs in (True, False):
+        r = run_round_both(B, n, N, ld, cs, off, int(rng.integers(1 << 40)), 5, peer, fused=False, outputs=outputs,
+                           tuning=[(B.TUNE_EXCHANGE_PATH, 3)])
+        check_round(r, N)
