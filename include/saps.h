@@ -101,7 +101,11 @@ saps_status saps_merge(saps_ctx* ctx, float* X, const int32_t* peer, const uint3
  * but with every element of X, G, V read once and X, V written once.  G == NULL skips the
  * local step (exchange-only round; V, lr, mu ignored).  idx, msg, K_dev may each be NULL
  * when the caller does not need that output; the capacity rule (K > msg_ld skips the round)
- * holds all the same, so msg_ld must cover K even then. */
+ * holds all the same, so msg_ld must cover K even then.
+ * Rounds are normally called with round = 1, 2, 3, ... and one seed: the kernels of a call therefore also count
+ * the kept coordinates of (seed, round + 1) on the side, and a next call with exactly that pair starts without
+ * the counting launch.  Any other pair simply counts for itself; results never depend on this.  Calls made
+ * under stream capture neither use nor produce such counts (a replay cannot know what ran before it). */
 saps_status saps_round(saps_ctx* ctx, float* X, const float* G, float* V, float lr, float mu,
                        uint64_t seed, uint64_t round, const int32_t* peer,
                        uint32_t* idx, float* msg, int64_t* K_dev);
@@ -166,7 +170,8 @@ enum {
     SAPS_TUNE_NONTEMPORAL = 2,     /* fused round and local step: 0 = plain, 1 = non-temporal loads/stores */
     SAPS_TUNE_EXCHANGE_PATH = 3,   /* exchange-only round: 0 = built-in choice by expected density, 1 = index list, 2 = tile walk,
                                       3 = index list, but whole tiles that keep at least every 12th coordinate are streamed */
-    SAPS_TUNE_BLOCKS_PER_CU = 4    /* fused round: resident 2-wave workgroups per compute unit, 3..16, 0 = no limit, -1 = built-in choice */
+    SAPS_TUNE_BLOCKS_PER_CU = 4,   /* fused round: resident 2-wave workgroups per compute unit, 3..16, 0 = no limit, -1 = built-in choice */
+    SAPS_TUNE_PREPARE_NEXT = 5     /* saps_round: 1 (default) = the kernels of round t also count the kept coordinates of round t + 1, 0 = never */
 };
 saps_status saps_set_tuning(saps_ctx* ctx, int32_t knob, int32_t value);
 

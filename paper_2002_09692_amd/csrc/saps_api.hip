@@ -71,8 +71,14 @@ struct saps_ctx {
     uint32_t n_walk = 0;
     // scratch
     uint32_t ngroups = 0;
-    uint32_t* d_tile = nullptr;         // ntiles kept counts, one per wave tile
-    uint32_t* d_grp = nullptr;          // ngroups counts, then exclusive bases after the scan
+    // Count buffers: [0] and [1] serve eager calls (a round's kernels count the next round into the one
+    // that the round itself does not read), [2] serves calls made under stream capture, so that replays
+    // of a graph never touch what eager calls have prepared.
+    uint32_t* d_tile[3] = {nullptr, nullptr, nullptr};   // ntiles kept counts, one per wave tile
+    uint32_t* d_grp[3] = {nullptr, nullptr, nullptr};    // ngroups counts, then exclusive bases after the scan
+    bool prep_valid = false;            // d_tile/d_grp[prep_buf] hold the counts of (prep_seed, prep_round)
+    uint64_t prep_seed = 0, prep_round = 0;
+    int prep_buf = 0;
     int64_t* d_K = nullptr;             // K of the most recent mask generation
     int32_t* d_flag = nullptr;          // sticky capacity flag
     double* d_partial = nullptr;        // one fp64 partial per workgroup of the consensus kernel
@@ -81,7 +87,7 @@ struct saps_ctx {
     Slot ring[RING];
     uint64_t calls = 0;
     // launch-shape knobs
-    int32_t ppb = 1, xcd_remap = 0, nontemporal = 1, exchange_path = 0, blocks_per_cu = -1;
+    int32_t ppb = 1, xcd_remap = 0, nontemporal = 1, exchange_path = 0, blocks_per_cu = -1, prepare_next = 1;
     // optional event pairs around the dominant kernel of a call
     bool profiling = false;
     std::vector<hipEvent_t> ev_pool;    // 2 events per record, created on demand
@@ -220,15 +226,39 @@ bool direct_bases(const saps_ctx* c) { return c->ngroups > 0 && c->ngroups <= DI
 
 // K1 (+ K2 unless the model is small): per-tile and per-group counts, exclusive group bases, K and
 // the capacity flag.  Returns what the position-consuming kernels need.
-saps_status enqueue_count_scan(saps_ctx* c, const MaskParams& P, int64_t* K_user, Bases* Bp) {
-    Bp->grp = c->d_grp; Bp->tile_cnt = c->d_tile; Bp->K_int = c->d_K; Bp->K_user = K_user; Bp->flag = c->d_flag;
+// `with_next`: the caller launches a kernel that can count the next round on the side (the fused round
+// kernel or the list exchange kernel); *Nx then says where, or holds nulls when there is nothing to prepare.
+saps_status enqueue_count_scan(saps_ctx* c, const MaskParams& P, uint64_t seed, uint64_t round, int64_t* K_user,
+                               Bases* Bp, bool with_next, NextCounts* Nx) {
+    hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+    if (c->d_tile[2]) SAPS_HIP(c, hipStreamIsCapturing(c->stream, &cap));
+    const bool capturing = cap != hipStreamCaptureStatusNone;
+    int buf = 0;
+    bool counted = false;                                  // the counts of (seed, round) are already there
+    if (capturing) {
+        buf = 2;
+    } else {
+        if (c->prep_valid && c->prep_seed == seed && c->prep_round == round) { buf = c->prep_buf; counted = true; }
+        c->prep_valid = false;
+    }
+    Bp->grp = c->d_grp[buf]; Bp->tile_cnt = c->d_tile[buf]; Bp->K_int = c->d_K; Bp->K_user = K_user; Bp->flag = c->d_flag;
     Bp->cap = c->msg_ld; Bp->ngroups = c->ngroups; Bp->direct = direct_bases(c) ? 1 : 0;
-    if (c->ngroups > 0)
-        hipLaunchKernelGGL(mask_count_kernel, dim3(c->ngroups), dim3(64 * GROUP), 0, c->stream, P, c->ntiles, c->d_tile, c->d_grp);
+    if (c->ngroups > 0 && !counted)
+        hipLaunchKernelGGL(mask_count_kernel, dim3(c->ngroups), dim3(64 * GROUP), 0, c->stream, P, c->ntiles, c->d_tile[buf], c->d_grp[buf]);
     if (!Bp->direct)
-        hipLaunchKernelGGL(group_scan_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_grp, c->ngroups, c->msg_ld,
+        hipLaunchKernelGGL(group_scan_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_grp[buf], c->ngroups, c->msg_ld,
                            c->d_K, K_user, c->d_flag);
     SAPS_HIP(c, hipGetLastError());
+    if (Nx) {
+        Nx->tile_cnt = nullptr; Nx->grp_cnt = nullptr; Nx->rnd0 = Nx->rnd1 = 0u; Nx->ngroups = c->ngroups;
+        if (with_next && !capturing && c->prepare_next && c->d_tile[1] && c->ngroups > 0) {
+            const int nb = buf == 0 ? 1 : 0;
+            const uint64_t next = round + 1;
+            Nx->tile_cnt = c->d_tile[nb]; Nx->grp_cnt = c->d_grp[nb];
+            Nx->rnd0 = (uint32_t)next; Nx->rnd1 = (uint32_t)(next >> 32);
+            c->prep_valid = true; c->prep_seed = seed; c->prep_round = next; c->prep_buf = nb;
+        }
+    }
     return SAPS_OK;
 }
 
@@ -249,36 +279,36 @@ uint32_t list_grid_x(const saps_ctx* c) {
 }
 
 template <int MODE, int PPB>
-void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, dim3 grid, bool mix_first) {
+void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, const NextCounts& Nx, dim3 grid, bool mix_first) {
     // measured best on the ResNet-18-sized workload: 6 two-wave workgroups per compute unit when
     // the momentum buffer is streamed too (ten 16-byte streams per lane), no cap otherwise
     const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : (MODE == 0 ? 6 : 0);
     const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(bpc);
     if (MODE != 2 && mix_first) {
         if (c->nontemporal)
-            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
         else
-            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
     } else {
         if (c->nontemporal)
-            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
         else
-            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U);
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
     }
 }
 
 template <int MODE>
-void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U, bool mix_first = false) {
+void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U, const NextCounts& Nx, bool mix_first = false) {
     int ppb = c->ppb;
     const uint32_t nblk = (c->ntiles + FUSED_WAVES - 1) / FUSED_WAVES;
     const uint32_t gx = c->xcd_remap ? 8u * ((nblk + 7u) / 8u) : nblk;
     A.xcd_remap = c->xcd_remap;
     const dim3 grid(gx, (uint32_t)((A.n_units + ppb - 1) / ppb));
     switch (ppb) {
-        case 1: launch_fused_nt<MODE, 1>(c, P, A, U, grid, mix_first); break;
-        case 2: launch_fused_nt<MODE, 2>(c, P, A, U, grid, mix_first); break;
-        case 4: launch_fused_nt<MODE, 4>(c, P, A, U, grid, mix_first); break;
-        default: launch_fused_nt<MODE, 8>(c, P, A, U, grid, mix_first); break;
+        case 1: launch_fused_nt<MODE, 1>(c, P, A, U, Nx, grid, mix_first); break;
+        case 2: launch_fused_nt<MODE, 2>(c, P, A, U, Nx, grid, mix_first); break;
+        case 4: launch_fused_nt<MODE, 4>(c, P, A, U, Nx, grid, mix_first); break;
+        default: launch_fused_nt<MODE, 8>(c, P, A, U, Nx, grid, mix_first); break;
     }
 }
 
@@ -301,7 +331,8 @@ saps_status round_impl(saps_ctx* c, float* X, const float* G, float* V, float lr
     if (s) return s;
     const MaskParams P = mask_params(c, seed, round);
     Bases Bp;
-    s = enqueue_count_scan(c, P, K_dev, &Bp);
+    NextCounts Nx;
+    s = enqueue_count_scan(c, P, seed, round, K_dev, &Bp, true, &Nx);
     if (s) return s;
     if (c->ntiles == 0) return SAPS_OK;
 
@@ -315,13 +346,13 @@ saps_status round_impl(saps_ctx* c, float* X, const float* G, float* V, float lr
 
     if (G) {
         profile_mark(c, false);
-        if (V) launch_fused<0>(c, P, A, U, mix_first); else launch_fused<1>(c, P, A, U, mix_first);
+        if (V) launch_fused<0>(c, P, A, U, Nx, mix_first); else launch_fused<1>(c, P, A, U, Nx, mix_first);
         profile_mark(c, true);
     } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 1.0 / 12.0 && c->density < 0.2)) {
         // measured on 32 x 11.2 M: the walk wins around c = 8 (0.62 vs 0.72 ms); for denser masks its
         // per-lane message stores cost more than the list's coalesced ones (c = 2, 4: 0.82-0.86 vs 0.73 ms)
         profile_mark(c, false);
-        launch_fused<2>(c, P, A, U);                   // dense masks: walk the tiles
+        launch_fused<2>(c, P, A, U, Nx);               // dense masks: walk the tiles
         profile_mark(c, true);
     } else {
         // sparse masks: go through the index list; path 3 streams the dense tiles of a mixed layout instead
@@ -339,18 +370,21 @@ saps_status round_impl(saps_ctx* c, float* X, const float* G, float* V, float lr
         const dim3 lgrid(list_grid_x(c), (uint32_t)n_units);
         if (hybrid) {
             if (c->stream_scatter)
-                hipLaunchKernelGGL((exchange_list_kernel<true, true>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits);
+                hipLaunchKernelGGL((exchange_list_kernel<true, true>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
             else
-                hipLaunchKernelGGL((exchange_list_kernel<false, true>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits);
+                hipLaunchKernelGGL((exchange_list_kernel<false, true>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
         } else {
             if (c->stream_scatter)
-                hipLaunchKernelGGL((exchange_list_kernel<true, false>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits);
+                hipLaunchKernelGGL((exchange_list_kernel<true, false>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
             else
-                hipLaunchKernelGGL((exchange_list_kernel<false, false>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits);
+                hipLaunchKernelGGL((exchange_list_kernel<false, false>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
         }
         profile_mark(c, true);
     }
-    SAPS_HIP(c, hipGetLastError());
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) {
+        c->prep_valid = false;                          // whatever was to count the next round may not have run
+        return hip_fail(c, e, "kernel launch");
+    }
     return SAPS_OK;
 }
 
@@ -440,8 +474,10 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
         chk(hipMemcpy(c->d_walk_tiles, walk_tiles.data(), sizeof(uint32_t) * walk_tiles.size(), hipMemcpyHostToDevice));
     if (e == hipSuccess) chk(hipMemcpy(c->d_walk_bits, walk_bits.data(), sizeof(uint32_t) * walk_bits.size(), hipMemcpyHostToDevice));
     if (e == hipSuccess) chk(hipMemcpy(c->d_grp_seg, grp_seg.data(), sizeof(uint32_t) * grp_seg.size(), hipMemcpyHostToDevice));
-    chk(hipMalloc(&c->d_tile, sizeof(uint32_t) * ((size_t)c->ntiles + 1)));
-    chk(hipMalloc(&c->d_grp, sizeof(uint32_t) * ((size_t)c->ngroups + 1)));
+    for (int b = 0; b < 3; ++b) {
+        chk(hipMalloc(&c->d_tile[b], sizeof(uint32_t) * ((size_t)c->ntiles + 1)));
+        chk(hipMalloc(&c->d_grp[b], sizeof(uint32_t) * ((size_t)c->ngroups + 1)));
+    }
     chk(hipMalloc(&c->d_K, sizeof(int64_t)));
     chk(hipMalloc(&c->d_partial, sizeof(double) * ((size_t)((L->N + 4 * BLOCK - 1) / (4 * BLOCK)) + 1)));
     chk(hipMalloc(&c->d_flag, sizeof(int32_t)));
@@ -467,7 +503,7 @@ saps_status saps_create(saps_ctx** out, const saps_layout* L, int64_t msg_ld, vo
 saps_status saps_destroy(saps_ctx* c) {
     if (!c) return SAPS_EINVAL;
     (void)hipStreamSynchronize(c->stream);
-    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_grp_seg); (void)hipFree(c->d_walk_tiles); (void)hipFree(c->d_walk_bits); (void)hipFree(c->d_tile); (void)hipFree(c->d_grp); (void)hipFree(c->d_K); (void)hipFree(c->d_partial);
+    (void)hipFree(c->d_seg_end); (void)hipFree(c->d_seg_T); (void)hipFree(c->d_grp_seg); (void)hipFree(c->d_walk_tiles); (void)hipFree(c->d_walk_bits); for (int b = 0; b < 3; ++b) { (void)hipFree(c->d_tile[b]); (void)hipFree(c->d_grp[b]); } (void)hipFree(c->d_K); (void)hipFree(c->d_partial);
     (void)hipFree(c->d_flag); (void)hipFree(c->d_idx); (void)hipFree(c->d_match);
     for (hipEvent_t e : c->ev_pool) (void)hipEventDestroy(e);
     for (int r = 0; r < RING; ++r) {
@@ -496,6 +532,9 @@ saps_status saps_set_tuning(saps_ctx* c, int32_t knob, int32_t value) {
         case SAPS_TUNE_EXCHANGE_PATH:
             if (value < 0 || value > 3) return fail(c, SAPS_EINVAL, "exchange path");
             c->exchange_path = value; return SAPS_OK;
+        case SAPS_TUNE_PREPARE_NEXT:
+            if (value != 0 && value != 1) return fail(c, SAPS_EINVAL, "prepare next");
+            c->prepare_next = value; c->prep_valid = false; return SAPS_OK;
         default: return fail(c, SAPS_EINVAL, "unknown knob");
     }
 }
@@ -532,7 +571,7 @@ saps_status saps_mask_compact(saps_ctx* c, const float* X, uint64_t seed, uint64
         return fail(c, SAPS_EINVAL, "misaligned pointer");
     const MaskParams P = mask_params(c, seed, round);
     Bases Bp;
-    saps_status s = enqueue_count_scan(c, P, K_dev, &Bp);
+    saps_status s = enqueue_count_scan(c, P, seed, round, K_dev, &Bp, false, nullptr);
     if (s) return s;
     if (c->ntiles == 0) return SAPS_OK;
     launch_idx_scatter(c, P, Bp, idx);
@@ -625,8 +664,8 @@ saps_status saps_round_static(int32_t n, int64_t N, int64_t ld, double c_ratio, 
     t.stream_scatter = stream_scatter_for(n, (double)N / 32.0 * (1.0 - std::pow(1.0 - t.density, 32.0)));
     t.d_K = reinterpret_cast<int64_t*>(base + ST_OFF_K);
     t.d_flag = reinterpret_cast<int32_t*>(base + ST_OFF_FLAG);
-    t.d_tile = reinterpret_cast<uint32_t*>(base + ST_OFF_TILE);
-    t.d_grp = reinterpret_cast<uint32_t*>(base + ST_OFF_GRP);
+    t.d_tile[0] = reinterpret_cast<uint32_t*>(base + ST_OFF_TILE);       // one buffer: every call counts for itself
+    t.d_grp[0] = reinterpret_cast<uint32_t*>(base + ST_OFF_GRP);
     t.d_idx = reinterpret_cast<uint32_t*>(base + ST_OFF_IDX);
     const saps_status st = round_impl(&t, X, G, V, lr, mu, seed, round, peer, idx, msg, K_dev, 0u);
     if (st != SAPS_OK) g_static_err = t.err;

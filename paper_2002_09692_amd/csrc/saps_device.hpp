@@ -202,6 +202,45 @@ __global__ __launch_bounds__(1024) void group_scan_kernel(uint32_t* __restrict__
     }
 }
 
+// ----------------------------------------- counts of the NEXT round, computed inside another kernel
+// The counts depend on (seed, round) only, so the kernels of round t can compute those of round t + 1 on
+// the side: the Philox arithmetic then hides under a kernel that waits for memory, and the next call starts
+// without K1.  One wave counts one whole group of 16 tiles by itself (no LDS, no barrier), waves take
+// groups round-robin by their index in the grid, and the low indices, which are dispatched first, come first.
+struct NextCounts {
+    uint32_t* tile_cnt;   // null: nothing to do
+    uint32_t* grp_cnt;
+    uint32_t rnd0, rnd1;  // the next round (same seed, thresholds and segments as the running one)
+    uint32_t ngroups;
+};
+
+__device__ __forceinline__ void count_next_round(const MaskParams& Pcur, const NextCounts& Nx, uint32_t ntiles,
+                                                 uint32_t wave_index, uint32_t waves_in_grid) {
+    if (!Nx.tile_cnt) return;
+    MaskParams P = Pcur;
+    P.rnd0 = Nx.rnd0; P.rnd1 = Nx.rnd1;
+    const uint32_t lane = threadIdx.x & 63u;
+    for (uint32_t g = wave_index; g < Nx.ngroups; g += waves_in_grid) {
+        const uint32_t t0 = g * GROUP;
+        uint32_t mine = 0u;                                   // lane r keeps the count of tile t0 + r
+#pragma unroll 1
+        for (uint32_t r = 0; r < (uint32_t)GROUP; ++r) {
+            const uint32_t tile = t0 + r;
+            if (tile >= ntiles) break;                        // wave-uniform
+            const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
+            const uint32_t m = mask4(P, tile, lane, seg0);
+            uint32_t total;
+            (void)wave_prefix(m, total);
+            if (lane == r) mine = total;
+        }
+        if (lane < (uint32_t)GROUP && t0 + lane < ntiles) Nx.tile_cnt[t0 + lane] = mine;
+        uint32_t sum = mine;                                  // lanes >= 16 hold zero
+#pragma unroll
+        for (int d = 1; d < GROUP; d <<= 1) sum += __shfl_xor(sum, d, 64);
+        if (lane == 0u) Nx.grp_cnt[g] = sum;
+    }
+}
+
 // Where the packed positions and K of the round come from.
 //   direct == 0: K2 ran; grp holds exclusive group bases and *K_int the total.
 //   direct == 1: small models (at most 256 groups): no K2 launch; grp still holds the group
@@ -414,35 +453,60 @@ __global__ __launch_bounds__(BLOCK) void merge_kernel(float* __restrict__ X, int
 // requested before anything is stored.  With SKIP, coordinates inside the tiles marked in walk_bits
 // (one bit per tile) are left to the tile walk K8w.
 template <bool STREAM, bool SKIP>
+__device__ __forceinline__ bool list_entry_load(const float* xi, const float* xp, const uint32_t* idx, int64_t k,
+                                                const uint32_t* walk_bits, uint32_t& j, float& a, float& b) {
+    j = idx[k];
+    if (SKIP) {
+        const uint32_t t = j / (uint32_t)TILE;
+        if ((walk_bits[t >> 5] >> (t & 31u)) & 1u) return false;
+    }
+    a = xi[j];
+    b = xp[j];                                       // unmatched worker: the same word again
+    return true;
+}
+
+template <bool STREAM>
+__device__ __forceinline__ void list_entry_store(float* xi, float* xp, float* mi, float* mp, bool paired, int64_t k,
+                                                 uint32_t j, float a, float b) {
+    if (mi) {
+        st1(mi + k, a);
+        if (paired) st1(mp + k, b);
+    }
+    if (paired) {
+        const float avg = (a + b) * 0.5f;
+        st1x<STREAM>(xi + j, avg);
+        st1x<STREAM>(xp + j, avg);
+    }
+}
+
+template <bool STREAM, bool SKIP>
 __global__ __launch_bounds__(BLOCK) void exchange_list_kernel(float* __restrict__ X, int64_t ld, Units U,
                                                               const uint32_t* __restrict__ idx,
                                                               const int64_t* __restrict__ K_int, int64_t cap,
                                                               float* __restrict__ msg, int64_t msg_ld,
-                                                              const uint32_t* __restrict__ walk_bits) {
+                                                              const uint32_t* __restrict__ walk_bits,
+                                                              MaskParams P, uint32_t ntiles, NextCounts Nx) {
     const int64_t K = *K_int;
-    if (K > cap) return;
     int32_t i, p;
     unit_at(U, blockIdx.y, i, p);
     float* xi = X + (int64_t)i * ld;
     float* xp = X + (int64_t)p * ld;
-    for (int64_t k = (int64_t)blockIdx.x * BLOCK + threadIdx.x; k < K; k += (int64_t)gridDim.x * BLOCK) {
-        const uint32_t j = idx[k];
-        if (SKIP) {
-            const uint32_t t = j / (uint32_t)TILE;
-            if ((walk_bits[t >> 5] >> (t & 31u)) & 1u) continue;
-        }
-        const float a = xi[j];
-        const float b = xp[j];                       // p == i: the same word again
-        if (msg) {
-            st1(msg + (int64_t)i * msg_ld + k, a);
-            if (p != i) st1(msg + (int64_t)p * msg_ld + k, b);
-        }
-        if (p != i) {
-            const float avg = (a + b) * 0.5f;
-            st1x<STREAM>(xi + j, avg);
-            st1x<STREAM>(xp + j, avg);
-        }
-    }
+    float* mi = msg ? msg + (int64_t)i * msg_ld : nullptr;
+    float* mp = msg ? msg + (int64_t)p * msg_ld : nullptr;
+    const int64_t stride = (int64_t)gridDim.x * BLOCK;
+    int64_t k = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+    // the first entry's gathers are requested before the next round is counted, so that the Philox
+    // arithmetic runs while they are in flight
+    uint32_t j = 0u;
+    float a = 0.f, b = 0.f;
+    const bool first = K <= cap && k < K && list_entry_load<STREAM, SKIP>(xi, xp, idx, k, walk_bits, j, a, b);
+    count_next_round(P, Nx, ntiles, (blockIdx.y * gridDim.x + blockIdx.x) * WAVES + (threadIdx.x >> 6),
+                     gridDim.x * gridDim.y * WAVES);
+    if (K > cap) return;
+    if (first) list_entry_store<STREAM>(xi, xp, mi, mp, p != i, k, j, a, b);
+    for (k += stride; k < K; k += stride)
+        if (list_entry_load<STREAM, SKIP>(xi, xp, idx, k, walk_bits, j, a, b))
+            list_entry_store<STREAM>(xi, xp, mi, mp, p != i, k, j, a, b);
 }
 
 // ------------------------------------------------------------------ K7: fused dense round
@@ -569,7 +633,9 @@ __device__ __forceinline__ void finish_unit(const FusedArgs& A, Operands& o, int
 }
 
 template <int MODE, int PPB, bool NT, bool MIXFIRST>
-__global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, FusedArgs A, Units U) {
+__global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, FusedArgs A, Units U, NextCounts Nx) {
+    count_next_round(P, Nx, A.ntiles, (blockIdx.y * gridDim.x + blockIdx.x) * FUSED_WAVES + (threadIdx.x >> 6),
+                     gridDim.x * gridDim.y * FUSED_WAVES);
     uint32_t blk = blockIdx.x;
     if (A.xcd_remap) {
         // workgroups are dealt round-robin to the 8 XCDs; give XCD x the range [x*per, (x+1)*per)
