@@ -74,8 +74,8 @@ typedef struct {
 
 /* Creates a context for one layout.  msg_ld = capacity of a packed message row (floats,
  * multiple of 4, >= 0).  hip_stream = hipStream_t to enqueue on (NULL = default stream).
- * Allocates the private scratch (about 4 bytes per 256 coordinates, 8 bytes per 1024 coordinates,
- * 4*msg_ld and 16*n bytes). */
+ * Allocates the private scratch (about 20 bytes per 256 coordinates: three sets of tile and group counts and
+ * the list of dense tiles; plus 4*msg_ld and 16*n bytes). */
 saps_status saps_create(saps_ctx** out, const saps_layout* layout, int64_t msg_ld, void* hip_stream);
 saps_status saps_destroy(saps_ctx* ctx);
 
