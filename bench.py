@@ -92,7 +92,7 @@ def measure(name: str, steps, warm: int, cpu_rounds, tune: str, with_cpu: bool, 
 
     ctx = binding.SapsContext(n, N, ld, cap, wl.seg_c, wl.seg_off)
     knobs = {"ppb": binding.TUNE_PAIRS_PER_BLOCK, "xcd": binding.TUNE_XCD_REMAP, "nt": binding.TUNE_NONTEMPORAL,
-             "path": binding.TUNE_EXCHANGE_PATH, "bpc": binding.TUNE_BLOCKS_PER_CU, "prep": binding.TUNE_PREPARE_NEXT}
+             "path": binding.TUNE_EXCHANGE_PATH, "bpc": binding.TUNE_BLOCKS_PER_CU, "prep": binding.TUNE_PREPARE_NEXT, "rpw": binding.TUNE_ROW_PER_WAVE}
     for kv in filter(None, tune.split(",")):
         k, v = kv.split("=")
         ctx.saps_set_tuning(knobs[k], int(v))

@@ -17,7 +17,7 @@ from .build import LIB
 
 OK, EINVAL, EMATCH, ECAPACITY, EHIP = 0, 1, 2, 3, 4
 ROUND_MIX_THEN_STEP = 1
-TUNE_PAIRS_PER_BLOCK, TUNE_XCD_REMAP, TUNE_NONTEMPORAL, TUNE_EXCHANGE_PATH, TUNE_BLOCKS_PER_CU, TUNE_PREPARE_NEXT = 0, 1, 2, 3, 4, 5
+TUNE_PAIRS_PER_BLOCK, TUNE_XCD_REMAP, TUNE_NONTEMPORAL, TUNE_EXCHANGE_PATH, TUNE_BLOCKS_PER_CU, TUNE_PREPARE_NEXT, TUNE_ROW_PER_WAVE = 0, 1, 2, 3, 4, 5, 6
 _NAMES = {OK: "SAPS_OK", EINVAL: "SAPS_EINVAL", EMATCH: "SAPS_EMATCH", ECAPACITY: "SAPS_ECAPACITY", EHIP: "SAPS_EHIP"}
 
 EXPORTS = ("saps_abi_version", "saps_create", "saps_destroy", "saps_sgd_step", "saps_mask_compact", "saps_merge",

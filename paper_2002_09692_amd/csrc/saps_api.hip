@@ -87,7 +87,7 @@ struct saps_ctx {
     Slot ring[RING];
     uint64_t calls = 0;
     // launch-shape knobs
-    int32_t ppb = 1, xcd_remap = 0, nontemporal = 1, exchange_path = 0, blocks_per_cu = -1, prepare_next = 1;
+    int32_t ppb = 1, xcd_remap = 0, nontemporal = 1, exchange_path = 0, blocks_per_cu = -1, prepare_next = 1, row_per_wave = 1;
     // optional event pairs around the dominant kernel of a call
     bool profiling = false;
     std::vector<hipEvent_t> ev_pool;    // 2 events per record, created on demand
@@ -297,6 +297,24 @@ void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const
     }
 }
 
+// K7p: one row per wave, one pair per workgroup (update rounds only).
+template <int MODE>
+void launch_fused_pair(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, const NextCounts& Nx, bool mix_first) {
+    // this shape wants every wave slot (measured on 32 x 11.2 M: 1.10 ms uncapped or at 14 workgroups per
+    // compute unit, 1.15 ms at 10, 1.59 ms at 6), so there is no built-in cap
+    const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : 0;
+    uint32_t lds = residency_lds_bytes(bpc);
+    if (lds > 2048u) lds -= 2048u;                     // the kernel's own 2 KB of LDS count towards the slice
+    const dim3 grid(c->ntiles, (uint32_t)A.n_units);
+    if (mix_first) {
+        if (c->nontemporal) hipLaunchKernelGGL((fused_pair_kernel<MODE, true, true>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
+        else hipLaunchKernelGGL((fused_pair_kernel<MODE, false, true>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
+    } else {
+        if (c->nontemporal) hipLaunchKernelGGL((fused_pair_kernel<MODE, true, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
+        else hipLaunchKernelGGL((fused_pair_kernel<MODE, false, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
+    }
+}
+
 template <int MODE>
 void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U, const NextCounts& Nx, bool mix_first = false) {
     int ppb = c->ppb;
@@ -346,7 +364,13 @@ saps_status round_impl(saps_ctx* c, float* X, const float* G, float* V, float lr
 
     if (G) {
         profile_mark(c, false);
-        if (V) launch_fused<0>(c, P, A, U, Nx, mix_first); else launch_fused<1>(c, P, A, U, Nx, mix_first);
+        // with a momentum buffer the row-per-wave shape is faster (1.10 against 1.12 ms on 32 x 11.2 M); without one,
+        // with three streams per wave, it is slower (0.49 against 0.41 ms on 32 x 6.65 M), so plain SGD needs the knob set to 2
+        if (((c->row_per_wave == 1 && V) || c->row_per_wave == 2) && c->ppb == 1 && !c->xcd_remap && n_units <= 65535) {
+            if (V) launch_fused_pair<0>(c, P, A, U, Nx, mix_first); else launch_fused_pair<1>(c, P, A, U, Nx, mix_first);
+        } else {
+            if (V) launch_fused<0>(c, P, A, U, Nx, mix_first); else launch_fused<1>(c, P, A, U, Nx, mix_first);
+        }
         profile_mark(c, true);
     } else if (c->exchange_path == 2 || (c->exchange_path == 0 && c->density >= 1.0 / 12.0 && c->density < 0.2)) {
         // measured on 32 x 11.2 M: the walk wins around c = 8 (0.62 vs 0.72 ms); for denser masks its
@@ -532,6 +556,9 @@ saps_status saps_set_tuning(saps_ctx* c, int32_t knob, int32_t value) {
         case SAPS_TUNE_EXCHANGE_PATH:
             if (value < 0 || value > 3) return fail(c, SAPS_EINVAL, "exchange path");
             c->exchange_path = value; return SAPS_OK;
+        case SAPS_TUNE_ROW_PER_WAVE:
+            if (value < 0 || value > 2) return fail(c, SAPS_EINVAL, "row per wave");
+            c->row_per_wave = value; return SAPS_OK;
         case SAPS_TUNE_PREPARE_NEXT:
             if (value != 0 && value != 1) return fail(c, SAPS_EINVAL, "prepare next");
             c->prepare_next = value; c->prep_valid = false; return SAPS_OK;

@@ -696,6 +696,88 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
     }
 }
 
+// ------------------------------------------- K7p: fused round, one row per wave, one pair per workgroup
+// The two waves of a workgroup own the two rows of a matched pair at the same tile: each wave streams its
+// own row (x, g, v in; x, v out: five 16-byte streams per lane instead of ten) and the two swap the values
+// of the tile through LDS to average the kept coordinates.  Fewer streams per wave means that the same
+// number of resident waves keeps fewer requests in flight, which is what the memory system rewards (a plain
+// update kernel measures 6.9 TB/s with one row per wave and 6.4 TB/s with two).  Both waves evaluate the mask.
+// Grid: x = tiles, y = units.  MODE 0: update with momentum buffer, 1: update without buffer.
+template <int MODE, bool NT, bool MIXFIRST>
+__global__ __launch_bounds__(FUSED_BLOCK) void fused_pair_kernel(MaskParams P, FusedArgs A, Units U, NextCounts Nx) {
+    static_assert(FUSED_WAVES == 2 && (MODE == 0 || MODE == 1), "one wave per row of a pair");
+    __shared__ f4 swap[2][64];
+    const uint32_t wave = threadIdx.x >> 6, lane = threadIdx.x & 63u;
+    count_next_round(P, Nx, A.ntiles, (blockIdx.y * gridDim.x + blockIdx.x) * FUSED_WAVES + wave,
+                     gridDim.x * gridDim.y * FUSED_WAVES);
+    const uint32_t tile = blockIdx.x;                                    // < ntiles by the grid
+    const uint32_t j0 = (tile * 64u + lane) << 2;
+    const bool live = j0 < P.N;
+    const uint32_t nval = live ? min(4u, P.N - j0) : 0u;
+    int32_t i, p;
+    unit_at(U, blockIdx.y, i, p);
+    const bool paired = (p != i);
+    const bool mine = live && (wave == 0u || paired);                    // the second wave of an unmatched worker idles
+    const int32_t row = (wave == 0u) ? i : p;
+    const int64_t e = (int64_t)row * A.ld + j0;
+    const f4 z = {0.f, 0.f, 0.f, 0.f};
+    f4 x = z, g = z, v = z;
+    if (mine) {
+        if (nval == 4u) {
+            x = ld4<NT>(A.X + e); g = ld4<NT>(A.G + e);
+            if (MODE == 0) v = ld4<NT>(A.V + e);
+        } else {
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+                if ((uint32_t)r < nval) { x[r] = A.X[e + r]; g[r] = A.G[e + r]; if (MODE == 0) v[r] = A.V[e + r]; }
+        }
+    }
+    const bool first_wave = (tile == 0u && blockIdx.y == 0 && wave == 0u);
+    const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
+    const uint32_t m = mask4(P, tile, lane, seg0);
+    uint32_t total;
+    int64_t K;
+    const uint32_t pos0 = tile_base_and_K(A.bases, tile, first_wave, K) + wave_prefix(m, total);
+    if (K > A.bases.cap) return;                                         // the same decision in both waves
+    if (blockIdx.y == 0 && wave == 0u && A.idx && m) {
+        uint32_t pos = pos0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if ((m >> r) & 1u) A.idx[pos++] = j0 + r;
+    }
+    if (!MIXFIRST) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { float xr = x[r], vr = v[r]; step1<MODE == 0>(xr, g[r], vr, A.lr, A.mu); x[r] = xr; v[r] = vr; }
+    }
+    if (total) swap[wave][lane] = x;                                     // what the peer averages with (wave-uniform branch)
+    if (mine && m && A.msg) {
+        uint32_t pos = pos0;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if ((m >> r) & 1u) A.msg[(int64_t)row * A.msg_ld + pos++] = x[r];
+    }
+    __syncthreads();
+    if (total && paired) {
+        const f4 o = swap[wave ^ 1u][lane];
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            if ((m >> r) & 1u) x[r] = (wave == 0u) ? (x[r] + o[r]) * 0.5f : (o[r] + x[r]) * 0.5f;
+    }
+    if (MIXFIRST) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) { float xr = x[r], vr = v[r]; step1<MODE == 0>(xr, g[r], vr, A.lr, A.mu); x[r] = xr; v[r] = vr; }
+    }
+    if (!mine) return;
+    if (nval == 4u) {
+        st4<NT>(A.X + e, x);
+        if (MODE == 0) st4<NT>(A.V + e, v);
+    } else {
+#pragma unroll
+        for (int r = 0; r < 3; ++r)
+            if ((uint32_t)r < nval) { A.X[e + r] = x[r]; if (MODE == 0) A.V[e + r] = v[r]; }
+    }
+}
+
 // ------------------------------- K8w: exchange-only round of the listed (dense) tiles by streaming
 // One wave per listed tile and chunk of units: the tile's 1 KB of both rows is read whole, the kept
 // coordinates are packed and averaged, and the tile is written back whole.  Where a mask keeps most

@@ -790,3 +790,15 @@ def test_hybrid_exchange_streams_dense_tiles_and_lists_the_rest(B, n):
         r = run_round_both(B, n, N, ld, cs, off, int(rng.integers(1 << 40)), 5, peer, fused=False, outputs=outputs,
                            tuning=[(B.TUNE_EXCHANGE_PATH, 3)])
         check_round(r, N)
+
+
+@pytest.mark.parametrize("n,N,ld,c", SHAPES)
+@pytest.mark.parametrize("rpw", [0, 1, 2])
+@pytest.mark.parametrize("with_v", [True, False])
+def test_fused_round_both_wave_shapes(B, n, N, ld, c, rpw, with_v):
+    """The update round either gives every wave both rows of a pair or gives each of a workgroup's two waves one
+    row (they swap the tile through LDS); same bits either way, with and without the momentum buffer, with an
+    unmatched worker, and in the mix-then-step order."""
+    peer = rand_peer(n, n + N, singles=1 if n > 2 else 0)
+    r = run_round_both(B, n, N, ld, c, None, 5, 3, peer, fused=True, with_v=with_v, tuning=[(B.TUNE_ROW_PER_WAVE, rpw)])
+    check_round(r, N)
