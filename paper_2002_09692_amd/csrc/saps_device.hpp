@@ -4,7 +4,8 @@
 // tiles of TILE = 256 coordinates; one wave owns one tile and lane l owns the four
 // coordinates 4*(64*tile + l) .. +3, which are exactly one Philox4x32-10 block, one 16-byte
 // access per row, and one nibble of mask bits.  Packed positions inside a tile come from
-// wave ballots alone, so no kernel needs LDS or a barrier.
+// wave ballots alone; LDS and a barrier appear only where waves have to meet (the group sum of the
+// counting kernel, the swap of a tile between the two rows of a pair).
 #pragma once
 
 #include <hip/hip_runtime.h>
