@@ -3,7 +3,7 @@
   cd /tmp && export TMPDIR=/tmp
   rocprofv3 --pmc FETCH_SIZE --output-format csv -d <dirF> -o pmc -- python3 bench.py --no-cpu --no-others --workload cfg3 --steps 5 --warmup 1
   rocprofv3 --pmc WRITE_SIZE --output-format csv -d <dirW> -o pmc -- python3 bench.py --no-cpu --no-others --workload cfg3 --steps 5 --warmup 1
-  python3 -m paper_2002_09692_amd.traffic --workload cfg3 --kernel fused_round_kernel \
+  python3 -m paper_2002_09692_amd.traffic --workload cfg3 --kernel fused_pair_kernel \
           --fetch <dirF>/.../pmc_counter_collection.csv --write <dirW>/.../pmc_counter_collection.csv
 
 Both counters are KiB per dispatch in the unit of the TCC request size; the scale to bytes is taken from the
