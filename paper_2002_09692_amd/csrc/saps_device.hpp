@@ -133,6 +133,13 @@ __device__ __forceinline__ void unit_at(const Units& U, int u, int32_t& i, int32
     }
 }
 
+// One word per tile: its kept count (at most 256) in the low half and, in the high half, the kept count of
+// the tiles in front of it inside its group of 16 (at most 3840), so that a wave finds the packed position
+// of its tile with one uniform load per level (tile word, group base) and no exchange between lanes.
+__device__ __forceinline__ uint32_t tile_word(uint32_t count, uint32_t before_in_group) { return count | (before_in_group << 16); }
+__device__ __forceinline__ uint32_t tile_count(uint32_t word) { return word & 0xFFFFu; }
+__device__ __forceinline__ uint32_t tile_before(uint32_t word) { return word >> 16; }
+
 // ------------------------------------------------ K1: per-tile and per-group kept counts
 // One workgroup of 16 waves per group of 16 tiles.
 __global__ __launch_bounds__(64 * GROUP) void mask_count_kernel(MaskParams P, uint32_t ntiles,
@@ -146,10 +153,14 @@ __global__ __launch_bounds__(64 * GROUP) void mask_count_kernel(MaskParams P, ui
         const int seg0 = (P.n_seg > 1) ? first_segment(P, tile) : 0;
         const uint32_t m = mask4(P, tile, threadIdx.x & 63u, seg0);
         (void)wave_prefix(m, total);
-        if ((threadIdx.x & 63u) == 0u) tile_cnt[tile] = total;
     }
     if ((threadIdx.x & 63u) == 0u) wsum[wave] = total;
     __syncthreads();
+    if ((threadIdx.x & 63u) == 0u && tile < ntiles) {
+        uint32_t before = 0u;                                  // kept coordinates of the group's tiles in front of this one
+        for (uint32_t w = 0; w < wave; ++w) before += wsum[w];
+        tile_cnt[tile] = tile_word(total, before);
+    }
     if (threadIdx.x == 0) {
         uint32_t g = 0u;
 #pragma unroll
@@ -234,11 +245,14 @@ __device__ __forceinline__ void count_next_round(const MaskParams& Pcur, const N
             (void)wave_prefix(m, total);
             if (lane == r) mine = total;
         }
-        if (lane < (uint32_t)GROUP && t0 + lane < ntiles) Nx.tile_cnt[t0 + lane] = mine;
-        uint32_t sum = mine;                                  // lanes >= 16 hold zero
+        uint32_t inc = mine;                                  // inclusive prefix over the 16 tiles (lanes >= 16 hold zero)
 #pragma unroll
-        for (int d = 1; d < GROUP; d <<= 1) sum += __shfl_xor(sum, d, 64);
-        if (lane == 0u) Nx.grp_cnt[g] = sum;
+        for (int d = 1; d < GROUP; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d, 64);
+            if ((int)lane >= d) inc += o;
+        }
+        if (lane < (uint32_t)GROUP && t0 + lane < ntiles) Nx.tile_cnt[t0 + lane] = tile_word(mine, inc - mine);
+        if (lane == (uint32_t)GROUP - 1u) Nx.grp_cnt[g] = inc;
     }
 }
 
@@ -286,16 +300,13 @@ __device__ __forceinline__ uint32_t group_base_and_K(const Bases& Bp, uint32_t g
     return Bp.grp[g];
 }
 
-// Packed position of the first kept coordinate of a tile (its group's base plus the counts of
-// the tiles in front of it inside the group, at most 15 words, one per lane, summed by swaps)
-// and the round's K.  Wave-uniform; every lane of the wave must call it.
+// Packed position of the first kept coordinate of a tile (its group's base plus the count of the
+// tiles in front of it inside the group, which its tile word carries) and the round's K.
+// Wave-uniform; every lane of the wave must call it.
 __device__ __forceinline__ uint32_t tile_base_and_K(const Bases& Bp, uint32_t tile, bool first_wave, int64_t& K) {
-    const uint32_t g = tile / GROUP, r = tile % GROUP, lane = threadIdx.x & 63u;
-    uint32_t v = (lane < r) ? Bp.tile_cnt[g * GROUP + lane] : 0u;
-    const uint32_t gbase = group_base_and_K(Bp, g, first_wave, K);
-#pragma unroll
-    for (int d = 1; d < GROUP; d <<= 1) v += __shfl_xor(v, d, 64);
-    return gbase + __builtin_amdgcn_readfirstlane(v);
+    const uint32_t word = Bp.tile_cnt[tile];
+    const uint32_t gbase = group_base_and_K(Bp, tile / GROUP, first_wave, K);
+    return gbase + tile_before(word);
 }
 
 // --------------------------------------------------------- K3: ascending index list idx
@@ -313,17 +324,11 @@ __global__ __launch_bounds__(BLOCK) void idx_scatter_kernel(MaskParams P, uint32
     if (tfirst >= ntiles) return;
     const uint32_t lane = threadIdx.x & 63u;
     const uint32_t g = tfirst / GROUP, t0 = g * GROUP;
-    const uint32_t cnt = (lane < (uint32_t)GROUP && t0 + lane < ntiles) ? Bp.tile_cnt[t0 + lane] : 0u;
+    const uint32_t word = (lane < (uint32_t)GROUP && t0 + lane < ntiles) ? Bp.tile_cnt[t0 + lane] : 0u;
+    const uint32_t cnt = tile_count(word), excl = tile_before(word);
     int64_t K;
     const uint32_t gbase = group_base_and_K(Bp, g, w == 0u, K);
     if (K > Bp.cap) return;
-    uint32_t inc = cnt;                                              // inclusive prefix over the group's 16 tiles
-#pragma unroll
-    for (int d = 1; d < GROUP; d <<= 1) {
-        const uint32_t o = __shfl_up(inc, d, 64);
-        if ((int)lane >= d) inc += o;
-    }
-    const uint32_t excl = inc - cnt;
     const uint32_t r0 = tfirst - t0;
     uint64_t todo = __ballot(cnt != 0u) & ((TPW == 16) ? 0xFFFFull : (((1ull << TPW) - 1ull) << r0));
     while (todo) {
@@ -653,7 +658,7 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_round_kernel(MaskParams P, 
     const int u_lo = blockIdx.y * PPB;
     const int u_hi = min(u_lo + PPB, A.n_units);
     const bool first_wave = (tile == 0u && blockIdx.y == 0);
-    if (MODE == 2 && !first_wave && A.bases.tile_cnt[tile] == 0u) return;   // nothing of this tile is exchanged
+    if (MODE == 2 && !first_wave && tile_count(A.bases.tile_cnt[tile]) == 0u) return;   // nothing of this tile is exchanged
 
     // the first unit's operands are requested before the mask arithmetic so that the Philox
     // rounds run while the loads are in flight
