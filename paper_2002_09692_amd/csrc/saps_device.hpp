@@ -156,16 +156,18 @@ __global__ __launch_bounds__(64 * GROUP) void mask_count_kernel(MaskParams P, ui
     }
     if ((threadIdx.x & 63u) == 0u) wsum[wave] = total;
     __syncthreads();
-    if ((threadIdx.x & 63u) == 0u && tile < ntiles) {
-        uint32_t before = 0u;                                  // kept coordinates of the group's tiles in front of this one
-        for (uint32_t w = 0; w < wave; ++w) before += wsum[w];
-        tile_cnt[tile] = tile_word(total, before);
-    }
-    if (threadIdx.x == 0) {
-        uint32_t g = 0u;
+    if (threadIdx.x < (uint32_t)GROUP) {
+        // the first 16 lanes write the group's 16 tile words with one store and the group count
+        const uint32_t cnt = wsum[threadIdx.x];
+        uint32_t inc = cnt;
 #pragma unroll
-        for (int w = 0; w < GROUP; ++w) g += wsum[w];
-        grp_cnt[blockIdx.x] = g;
+        for (int d = 1; d < GROUP; d <<= 1) {
+            const uint32_t o = __shfl_up(inc, d, 64);
+            if ((int)threadIdx.x >= d) inc += o;
+        }
+        const uint32_t t = blockIdx.x * GROUP + threadIdx.x;
+        if (t < ntiles) tile_cnt[t] = tile_word(cnt, inc - cnt);
+        if (threadIdx.x == (uint32_t)GROUP - 1u) grp_cnt[blockIdx.x] = inc;
     }
 }
 
