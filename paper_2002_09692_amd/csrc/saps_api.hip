@@ -575,7 +575,10 @@ saps_status saps_sgd_step(saps_ctx* c, float* X, const float* G, float* V, float
     const uint32_t gx = (uint32_t)(((c->N + 3) / 4 + BLOCK - 1) / BLOCK);
     const dim3 grid(gx, (uint32_t)c->n);
     const uint32_t N = (uint32_t)c->N;
-    const uint32_t SGD_LDS = residency_lds_bytes(6);          // 6 workgroups of 4 waves per compute unit
+    // resident 4-wave workgroups per compute unit: 3 with the momentum buffer (five 16-byte streams per lane), 5 without
+    // (three streams), i.e. about sixty 1 KB requests in flight per compute unit.  Measured on 32 x 11.2 M: with the
+    // buffer 6.64 TB/s at 3, 6.49 at 4, 6.19 at 6, 6.06 uncapped; without it 6.67 at 5, 6.57 at 4, 6.49 uncapped
+    const uint32_t SGD_LDS = residency_lds_bytes(c->blocks_per_cu >= 0 ? c->blocks_per_cu : (V ? 3 : 5));
     profile_mark(c, false);
     if (V) {
         if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, dim3(BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
