@@ -709,9 +709,11 @@ saps_status saps_consensus(saps_ctx* c, const float* X, float* mean_out, double*
         return fail(c, SAPS_EINVAL, "X/mean/D null or misaligned");
     const uint32_t blocks = (uint32_t)((c->N + 4 * BLOCK - 1) / (4 * BLOCK));
     if (blocks > 0) {
+        // 3 four-wave workgroups per compute unit (8 rows in flight per lane): 6.81 against 6.62 TB/s uncapped on 32 x 11.2 M
+        const uint32_t clds = residency_lds_bytes(c->blocks_per_cu >= 0 ? c->blocks_per_cu : 3);
         profile_mark(c, false);
-        if (c->nontemporal) hipLaunchKernelGGL(consensus_kernel<true>, dim3(blocks), dim3(BLOCK), 0, c->stream, X, c->ld, (uint32_t)c->N, c->n, mean_out, c->d_partial);
-        else hipLaunchKernelGGL(consensus_kernel<false>, dim3(blocks), dim3(BLOCK), 0, c->stream, X, c->ld, (uint32_t)c->N, c->n, mean_out, c->d_partial);
+        if (c->nontemporal) hipLaunchKernelGGL(consensus_kernel<true>, dim3(blocks), dim3(BLOCK), clds, c->stream, X, c->ld, (uint32_t)c->N, c->n, mean_out, c->d_partial);
+        else hipLaunchKernelGGL(consensus_kernel<false>, dim3(blocks), dim3(BLOCK), clds, c->stream, X, c->ld, (uint32_t)c->N, c->n, mean_out, c->d_partial);
         profile_mark(c, true);
     }
     hipLaunchKernelGGL(consensus_finish_kernel, dim3(1), dim3(1024), 0, c->stream, c->d_partial, blocks, D_dev);
