@@ -284,16 +284,17 @@ void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const
     // the momentum buffer is streamed too (ten 16-byte streams per lane), no cap otherwise
     const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : (MODE == 0 ? 6 : 0);
     const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(bpc);
+    const dim3 block(64 * fused_round_waves(MODE));
     if (MODE != 2 && mix_first) {
         if (c->nontemporal)
-            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, MODE != 2>), grid, block, lds, c->stream, P, A, U, Nx);
         else
-            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, MODE != 2>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, MODE != 2>), grid, block, lds, c->stream, P, A, U, Nx);
     } else {
         if (c->nontemporal)
-            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, true, false>), grid, block, lds, c->stream, P, A, U, Nx);
         else
-            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, false>), grid, dim3(FUSED_BLOCK), lds, c->stream, P, A, U, Nx);
+            hipLaunchKernelGGL((fused_round_kernel<MODE, PPB, false, false>), grid, block, lds, c->stream, P, A, U, Nx);
     }
 }
 
@@ -318,7 +319,8 @@ void launch_fused_pair(saps_ctx* c, const MaskParams& P, const FusedArgs& A, con
 template <int MODE>
 void launch_fused(saps_ctx* c, const MaskParams& P, FusedArgs& A, const Units& U, const NextCounts& Nx, bool mix_first = false) {
     int ppb = c->ppb;
-    const uint32_t nblk = (c->ntiles + FUSED_WAVES - 1) / FUSED_WAVES;
+    constexpr uint32_t NW = (uint32_t)fused_round_waves(MODE);
+    const uint32_t nblk = (c->ntiles + NW - 1) / NW;
     const uint32_t gx = c->xcd_remap ? 8u * ((nblk + 7u) / 8u) : nblk;
     A.xcd_remap = c->xcd_remap;
     const dim3 grid(gx, (uint32_t)((A.n_units + ppb - 1) / ppb));
@@ -551,7 +553,7 @@ saps_status saps_set_tuning(saps_ctx* c, int32_t knob, int32_t value) {
             if (value != 0 && value != 1) return fail(c, SAPS_EINVAL, "nontemporal");
             c->nontemporal = value; return SAPS_OK;
         case SAPS_TUNE_BLOCKS_PER_CU:
-            if (value != -1 && value != 0 && (value < 3 || value > 16)) return fail(c, SAPS_EINVAL, "blocks per CU");
+            if (value != -1 && value != 0 && (value < 3 || value > 32)) return fail(c, SAPS_EINVAL, "blocks per CU");
             c->blocks_per_cu = value; return SAPS_OK;
         case SAPS_TUNE_EXCHANGE_PATH:
             if (value < 0 || value > 3) return fail(c, SAPS_EINVAL, "exchange path");
