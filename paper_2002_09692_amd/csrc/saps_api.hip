@@ -574,20 +574,20 @@ saps_status saps_sgd_step(saps_ctx* c, float* X, const float* G, float* V, float
     if (!X || !G || !aligned16(X) || !aligned16(G) || !aligned16(V)) return fail(c, SAPS_EINVAL, "X/G/V null or misaligned");
     if (!V && mu != 0.0f) return fail(c, SAPS_EINVAL, "momentum needs V");
     if (c->N == 0) return SAPS_OK;
-    const uint32_t gx = (uint32_t)(((c->N + 3) / 4 + BLOCK - 1) / BLOCK);
+    const uint32_t gx = (uint32_t)(((c->N + 3) / 4 + STREAM_BLOCK - 1) / STREAM_BLOCK);
     const dim3 grid(gx, (uint32_t)c->n);
     const uint32_t N = (uint32_t)c->N;
-    // resident 4-wave workgroups per compute unit: 3 with the momentum buffer (five 16-byte streams per lane), 5 without
-    // (three streams), i.e. about sixty 1 KB requests in flight per compute unit.  Measured on 32 x 11.2 M: with the
-    // buffer 6.64 TB/s at 3, 6.49 at 4, 6.19 at 6, 6.06 uncapped; without it 6.67 at 5, 6.57 at 4, 6.49 uncapped
-    const uint32_t SGD_LDS = residency_lds_bytes(c->blocks_per_cu >= 0 ? c->blocks_per_cu : (V ? 3 : 5));
+    // resident one-wave workgroups per compute unit: 10 with the momentum buffer (five 16-byte streams per lane), 16 without
+    // (three streams), i.e. about fifty 1 KB requests in flight per compute unit.  Measured on 32 x 11.2 M: with the
+    // buffer 6.77 TB/s at 10, 6.62 at 8, 6.49 at 16, 6.21 uncapped; without it 6.76 at 16, 6.14 at 12, 6.66 uncapped
+    const uint32_t SGD_LDS = residency_lds_bytes(c->blocks_per_cu >= 0 ? c->blocks_per_cu : (V ? 10 : 16));
     profile_mark(c, false);
     if (V) {
-        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, dim3(BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
-        else hipLaunchKernelGGL((sgd_kernel<true, false>), grid, dim3(BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
+        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, dim3(STREAM_BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
+        else hipLaunchKernelGGL((sgd_kernel<true, false>), grid, dim3(STREAM_BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
     } else {
-        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<false, true>), grid, dim3(BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
-        else hipLaunchKernelGGL((sgd_kernel<false, false>), grid, dim3(BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
+        if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<false, true>), grid, dim3(STREAM_BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
+        else hipLaunchKernelGGL((sgd_kernel<false, false>), grid, dim3(STREAM_BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
     }
     profile_mark(c, true);
     SAPS_HIP(c, hipGetLastError());
@@ -763,11 +763,11 @@ saps_status saps_stream_copy(saps_ctx* c, float* dst, const float* src, int64_t 
     if (!dst || !src || count < 0 || (count & 3) || !aligned16(dst) || !aligned16(src)) return fail(c, SAPS_EINVAL, "copy arguments");
     if (count == 0) return SAPS_OK;
     const int64_t c4 = count / 4;
-    const int64_t blocks = (c4 + BLOCK - 1) / BLOCK;
+    const int64_t blocks = (c4 + STREAM_BLOCK - 1) / STREAM_BLOCK;
     if (blocks > 0x7FFFFFFFll) return fail(c, SAPS_EINVAL, "copy too large");
     profile_mark(c, false);
-    if (c->nontemporal) hipLaunchKernelGGL(stream_copy_kernel<true>, dim3((uint32_t)blocks), dim3(BLOCK), 0, c->stream, dst, src, c4);
-    else hipLaunchKernelGGL(stream_copy_kernel<false>, dim3((uint32_t)blocks), dim3(BLOCK), 0, c->stream, dst, src, c4);
+    if (c->nontemporal) hipLaunchKernelGGL(stream_copy_kernel<true>, dim3((uint32_t)blocks), dim3(STREAM_BLOCK), 0, c->stream, dst, src, c4);
+    else hipLaunchKernelGGL(stream_copy_kernel<false>, dim3((uint32_t)blocks), dim3(STREAM_BLOCK), 0, c->stream, dst, src, c4);
     profile_mark(c, true);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;

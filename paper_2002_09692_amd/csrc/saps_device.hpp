@@ -17,6 +17,7 @@ constexpr int BLOCK = 256;          // lanes per workgroup (4 waves)
 constexpr int WAVES = BLOCK / 64;
 constexpr int TILE = 64 * 4;        // coordinates per tile: one wave, one Philox block per lane
 constexpr int GROUP = 16;           // tiles per group: the counting kernel's workgroup of 16 waves
+constexpr int STREAM_BLOCK = 64;    // lanes per workgroup of the plain streaming kernels (local step, copy): one wave
 constexpr int MAX_INLINE_UNITS = 128;
 constexpr int FUSED_BLOCK = 128;    // lanes per workgroup of the fused round kernels (2 waves)
 constexpr int FUSED_WAVES = FUSED_BLOCK / 64;
@@ -401,9 +402,9 @@ template <bool HAS_V> __device__ __forceinline__ void step1(float& x, float g, f
 
 // --------------------------------------------------------------------- K4: local update
 template <bool HAS_V, bool NT>
-__global__ __launch_bounds__(BLOCK) void sgd_kernel(float* __restrict__ X, const float* __restrict__ G,
-                                                    float* __restrict__ V, int64_t ld, uint32_t N, float lr, float mu) {
-    const uint32_t q = blockIdx.x * BLOCK + threadIdx.x;
+__global__ __launch_bounds__(STREAM_BLOCK) void sgd_kernel(float* __restrict__ X, const float* __restrict__ G,
+                                                           float* __restrict__ V, int64_t ld, uint32_t N, float lr, float mu) {
+    const uint32_t q = blockIdx.x * STREAM_BLOCK + threadIdx.x;
     const uint32_t j0 = q << 2;
     if (j0 >= N) return;
     const int64_t e = (int64_t)blockIdx.y * ld + j0;
@@ -936,9 +937,9 @@ __global__ __launch_bounds__(1024) void consensus_finish_kernel(const double* __
 
 // --------------------------------------------------------- bandwidth yardstick (a copy)
 template <bool NT>
-__global__ __launch_bounds__(BLOCK) void stream_copy_kernel(float* __restrict__ dst, const float* __restrict__ src,
-                                                            int64_t count4) {
-    const int64_t q = (int64_t)blockIdx.x * BLOCK + threadIdx.x;
+__global__ __launch_bounds__(STREAM_BLOCK) void stream_copy_kernel(float* __restrict__ dst, const float* __restrict__ src,
+                                                                   int64_t count4) {
+    const int64_t q = (int64_t)blockIdx.x * STREAM_BLOCK + threadIdx.x;
     if (q < count4) st4<NT>(dst + 4 * q, ld4<NT>(src + 4 * q));
 }
 
