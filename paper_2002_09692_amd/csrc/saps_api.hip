@@ -192,12 +192,13 @@ void launch_idx_scatter(saps_ctx* c, const MaskParams& P, const Bases& Bp, uint3
 constexpr double SCATTER_WRITEBACK_MAX_BYTES = 32e6;
 bool stream_scatter_for(int32_t n, double expected_lines) { return (double)n * expected_lines * 128.0 > SCATTER_WRITEBACK_MAX_BYTES; }
 
-// The fused round kernel runs fastest with few resident waves per compute unit (fewer DRAM
-// pages open at once: measured best at 12 waves).  Residency is capped by giving each
-// workgroup a slice of the 160 KB LDS that it never touches: 156 KB / blocks leaves room for
-// exactly that many workgroups.
+// The streaming kernels run fastest with a moderate number of resident waves per compute unit (more requests in
+// flight than the DRAM interface has credits for only queue up in front of it).  Residency is capped by giving
+// each workgroup a slice of the 160 KB LDS that it never touches.  LDS is handed out in granules of 1280 bytes
+// (128 per compute unit), so a slice of floor(128 / blocks) granules admits floor(128 / granules) workgroups:
+// exactly `blocks` for 1..12, 14, 16, 18, 21, 25, 32, the next such value otherwise.
 uint32_t residency_lds_bytes(int32_t blocks_per_cu) {
-    return blocks_per_cu > 0 ? (uint32_t)(156 / blocks_per_cu) * 1024u : 0u;
+    return blocks_per_cu > 0 ? (uint32_t)(128 / blocks_per_cu) * 1280u : 0u;
 }
 
 constexpr size_t MAX_PROFILE_RECORDS = 4096;
@@ -280,9 +281,10 @@ uint32_t list_grid_x(const saps_ctx* c) {
 
 template <int MODE, int PPB>
 void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, const NextCounts& Nx, dim3 grid, bool mix_first) {
-    // measured best on the ResNet-18-sized workload: 6 two-wave workgroups per compute unit when
-    // the momentum buffer is streamed too (ten 16-byte streams per lane), no cap otherwise
-    const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : (MODE == 0 ? 6 : 0);
+    // measured best: 5 two-wave workgroups per compute unit when the momentum buffer is streamed too (ten 16-byte
+    // streams per lane; 32 x 11.2 M: 1.107 ms against 1.127 at 6, 1.168 at 4), 16 one-wave workgroups without it
+    // (six streams per lane, four waves per SIMD; 32 x 6.65 M: 0.386 ms against 0.425 at 12, 0.401 at 21, 0.405 uncapped)
+    const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : (MODE == 0 ? 5 : 16);
     const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(bpc);
     const dim3 block(64 * fused_round_waves(MODE));
     if (MODE != 2 && mix_first) {
@@ -301,9 +303,9 @@ void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const
 // K7p: one row per wave, one pair per workgroup (update rounds only).
 template <int MODE>
 void launch_fused_pair(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, const NextCounts& Nx, bool mix_first) {
-    // this shape wants every wave slot (measured on 32 x 11.2 M: 1.10 ms uncapped or at 14 workgroups per
-    // compute unit, 1.15 ms at 10, 1.59 ms at 6), so there is no built-in cap
-    const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : 0;
+    // measured on 32 x 11.2 M: 1.086-1.092 ms at 9 or 10 two-wave workgroups per compute unit (five waves per SIMD),
+    // 1.10 at 11, 1.13 at 8 and from 12 on
+    const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : 10;
     uint32_t lds = residency_lds_bytes(bpc);
     if (lds > 2048u) lds -= 2048u;                     // the kernel's own 2 KB of LDS count towards the slice
     const dim3 grid(c->ntiles, (uint32_t)A.n_units);

@@ -279,6 +279,19 @@ struct Bases {
 };
 constexpr uint32_t DIRECT_MAX_GROUPS = 256;
 
+// Wave-uniform words that no kernel writes while it reads them (the counts and bases of the running round; the
+// kernels that count the next round on the side write the other buffer): read as constant memory, so that they
+// travel through the scalar cache and neither queue behind the wave's 16-byte streams nor wait for them (vector
+// loads return in order).  A wave then gets to its stores sooner, and fewer resident waves keep the memory busy.
+__device__ __forceinline__ uint32_t uniform_u32(const uint32_t* p, uint32_t index) {
+    typedef const __attribute__((address_space(4))) uint32_t* cptr;
+    return ((cptr)(uintptr_t)p)[__builtin_amdgcn_readfirstlane(index)];
+}
+__device__ __forceinline__ int64_t uniform_i64(const int64_t* p) {
+    typedef const __attribute__((address_space(4))) int64_t* cptr;
+    return *(cptr)(uintptr_t)p;
+}
+
 // Packed position of the first kept coordinate of group g and the round's K.  Wave-uniform; every
 // lane of the wave must call it.
 __device__ __forceinline__ uint32_t group_base_and_K(const Bases& Bp, uint32_t g, bool first_wave, int64_t& K) {
@@ -302,15 +315,15 @@ __device__ __forceinline__ uint32_t group_base_and_K(const Bases& Bp, uint32_t g
         }
         return __builtin_amdgcn_readfirstlane(before);
     }
-    K = *Bp.K_int;
-    return Bp.grp[g];
+    K = uniform_i64(Bp.K_int);
+    return uniform_u32(Bp.grp, g);
 }
 
 // Packed position of the first kept coordinate of a tile (its group's base plus the count of the
 // tiles in front of it inside the group, which its tile word carries) and the round's K.
 // Wave-uniform; every lane of the wave must call it.
 __device__ __forceinline__ uint32_t tile_base_and_K(const Bases& Bp, uint32_t tile, bool first_wave, int64_t& K) {
-    const uint32_t word = Bp.tile_cnt[tile];
+    const uint32_t word = uniform_u32(Bp.tile_cnt, tile);
     const uint32_t gbase = group_base_and_K(Bp, tile / GROUP, first_wave, K);
     return gbase + tile_before(word);
 }
