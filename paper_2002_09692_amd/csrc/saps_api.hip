@@ -201,6 +201,29 @@ uint32_t residency_lds_bytes(int32_t blocks_per_cu) {
     return blocks_per_cu > 0 ? (uint32_t)(128 / blocks_per_cu) * 1280u : 0u;
 }
 
+// Compute units of a device, asked once per device.
+int32_t compute_units(int device) {
+    static std::mutex mu;
+    static int32_t cache[STATIC_MAX_DEVICES] = {};
+    if (device < 0 || device >= STATIC_MAX_DEVICES) return 256;
+    std::lock_guard<std::mutex> g(mu);
+    if (!cache[device]) {
+        int v = 0;
+        if (hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess || v <= 0) v = 256;
+        cache[device] = v;
+    }
+    return cache[device];
+}
+
+// Workgroups per compute unit of a streaming kernel: the caller's knob, else the kernel's built-in cap, but only
+// for grids that turn the resident set over at least 32 times: a short grid loses more in its last, partly filled
+// turn than the cap gains (fused round with buffer, 32 x 1.0 M: 0.111 ms capped, 0.105 uncapped; 32 x 3.0 M: 0.290
+// against 0.294; 2 x 11.2 M: 0.081 against 0.079; 8 x 11.2 M: 0.280 against 0.283).
+int32_t residency_for(const saps_ctx* c, int32_t builtin, uint64_t workgroups) {
+    if (c->blocks_per_cu >= 0) return c->blocks_per_cu;
+    return workgroups >= 32ull * (uint64_t)compute_units(c->device) * (uint64_t)builtin ? builtin : 0;
+}
+
 constexpr size_t MAX_PROFILE_RECORDS = 4096;
 
 // Records an event on the stream if profiling is on; `second` closes the pair opened before.
@@ -284,7 +307,7 @@ void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const
     // measured best: 5 two-wave workgroups per compute unit when the momentum buffer is streamed too (ten 16-byte
     // streams per lane; 32 x 11.2 M: 1.107 ms against 1.127 at 6, 1.168 at 4), 16 one-wave workgroups without it
     // (six streams per lane, four waves per SIMD; 32 x 6.65 M: 0.386 ms against 0.425 at 12, 0.401 at 21, 0.405 uncapped)
-    const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : (MODE == 0 ? 5 : 16);
+    const int32_t bpc = residency_for(c, MODE == 0 ? 5 : 16, (uint64_t)grid.x * grid.y);
     const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(bpc);
     const dim3 block(64 * fused_round_waves(MODE));
     if (MODE != 2 && mix_first) {
@@ -303,9 +326,9 @@ void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const
 // K7p: one row per wave, one pair per workgroup (update rounds only).
 template <int MODE>
 void launch_fused_pair(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, const NextCounts& Nx, bool mix_first) {
-    // measured on 32 x 11.2 M: 1.086-1.092 ms at 9 or 10 two-wave workgroups per compute unit (five waves per SIMD),
-    // 1.10 at 11, 1.13 at 8 and from 12 on
-    const int32_t bpc = c->blocks_per_cu >= 0 ? c->blocks_per_cu : 10;
+    // measured on 32 x 11.2 M: 1.085-1.088 ms at 9 two-wave workgroups per compute unit, 1.091-1.092 at 10, 1.10 at 11,
+    // 1.13 at 8 and from 12 on; 9 is also the best on 128 x 11.2 M, 32 x 25.6 M, 32 x 100 M and 64 x 6.65 M (by 0.5-1 % over 10)
+    const int32_t bpc = residency_for(c, 9, (uint64_t)c->ntiles * (uint64_t)A.n_units);
     uint32_t lds = residency_lds_bytes(bpc);
     if (lds > 2048u) lds -= 2048u;                     // the kernel's own 2 KB of LDS count towards the slice
     const dim3 grid(c->ntiles, (uint32_t)A.n_units);
@@ -582,7 +605,7 @@ saps_status saps_sgd_step(saps_ctx* c, float* X, const float* G, float* V, float
     // resident one-wave workgroups per compute unit: 10 with the momentum buffer (five 16-byte streams per lane), 16 without
     // (three streams), i.e. about fifty 1 KB requests in flight per compute unit.  Measured on 32 x 11.2 M: with the
     // buffer 6.77 TB/s at 10, 6.62 at 8, 6.49 at 16, 6.21 uncapped; without it 6.76 at 16, 6.14 at 12, 6.66 uncapped
-    const uint32_t SGD_LDS = residency_lds_bytes(c->blocks_per_cu >= 0 ? c->blocks_per_cu : (V ? 10 : 16));
+    const uint32_t SGD_LDS = residency_lds_bytes(residency_for(c, V ? 10 : 16, (uint64_t)gx * (uint64_t)c->n));
     profile_mark(c, false);
     if (V) {
         if (c->nontemporal) hipLaunchKernelGGL((sgd_kernel<true, true>), grid, dim3(STREAM_BLOCK), SGD_LDS, c->stream, X, G, V, c->ld, N, lr, mu);
