@@ -304,6 +304,34 @@ def measure(name: str, steps, warm: int, cpu_rounds, tune: str, with_cpu: bool, 
             "algorithmic_GBps_with_mean_output": (4.0 * n * N + 4.0 * N) / (cons_ms["with_mean_output"] * 1e-3) / 1e9,
             "bytes_per_unit": "4 B per worker-coordinate read (+ 4 B per coordinate when the mean is written)"}
 
+        # the same round as three separate entry points (local step, mask + compaction, merge): what the fusion saves
+        if wl.fused:
+            def timed(call, reps=10):
+                for _ in range(2):
+                    call()
+                e0 = torch.cuda.Event(enable_timing=True); e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    call()
+                e1.record()
+                torch.cuda.synchronize()
+                return e0.elapsed_time(e1) / reps
+            Kd = Ks[0:1]
+            t_s = t_last + 1
+            ms_step = timed(lambda: ctx.saps_sgd_step(X, G, V, lr, mu))
+            ms_compact = timed(lambda: ctx.saps_mask_compact(X, seed, t_s, idx, msg, Kd))
+            Ku = int(Kd.item())
+            ms_merge = timed(lambda: ctx.saps_merge(X, peers[t_s], idx, msg, Kd))
+            assert ctx.saps_poll_status()[0] == 0
+            b_step = (20.0 if wl.has_buffer else 12.0) * n * N
+            out["stages_unfused"] = {
+                "saps_sgd_step_ms": ms_step, "saps_sgd_step_GBps": b_step / (ms_step * 1e-3) / 1e9,
+                "saps_mask_compact_ms": ms_compact, "saps_mask_compact_algorithmic_bytes": 8.0 * n * Ku + 4.0 * Ku,
+                "saps_merge_ms": ms_merge, "saps_merge_algorithmic_bytes": 12.0 * n * Ku,
+                "sum_ms": ms_step + ms_compact + ms_merge, "fused_round_ms": ms_per_step,
+                "note": "each entry point timed alone with HIP events over 10 calls on the final state; the two exchange "
+                        "stages touch one 128-byte line per kept value (line-granular, like the exchange-only rounds)"}
+
     ctx.close()
     if selector is not None:
         selector.close()
@@ -403,6 +431,7 @@ def main() -> int:
         "graph_replay_ms_per_step": m.get("graph_replay_ms_per_step"),
         "K_mean": m["K_mean"],
         "consensus": m.get("consensus"),
+        "stages_unfused": m.get("stages_unfused"),
         "traffic_per_worker_bytes": {"measured_8K": 8.0 * m["K_mean"], "paper_2N_over_c_x4B": 8.0 * cfg["expected_K"]},
         "other_workloads": others,
         "kernel_source_sha16": kernel_source_sha16(),
