@@ -305,8 +305,8 @@ uint32_t list_grid_x(const saps_ctx* c) {
 template <int MODE, int PPB>
 void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, const NextCounts& Nx, dim3 grid, bool mix_first) {
     // measured best: 5 two-wave workgroups per compute unit when the momentum buffer is streamed too (ten 16-byte
-    // streams per lane; 32 x 11.2 M: 1.107 ms against 1.127 at 6, 1.168 at 4), 16 one-wave workgroups without it
-    // (six streams per lane, four waves per SIMD; 32 x 6.65 M: 0.386 ms against 0.425 at 12, 0.401 at 21, 0.405 uncapped)
+    // streams per lane; 32 x 11.2 M: 1.100 ms against 1.110 at 6, 1.165 at 4), 16 one-wave workgroups without it
+    // (six streams per lane; 32 x 6.65 M: 0.382 ms against 0.419 at 12, 0.392 at 14, 0.386 at 18, 0.390 at 21, 0.405 uncapped)
     const int32_t bpc = residency_for(c, MODE == 0 ? 5 : 16, (uint64_t)grid.x * grid.y);
     const uint32_t lds = (MODE == 2) ? 0u : residency_lds_bytes(bpc);
     const dim3 block(64 * fused_round_waves(MODE));
@@ -326,8 +326,8 @@ void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const
 // K7p: one row per wave, one pair per workgroup (update rounds only).
 template <int MODE>
 void launch_fused_pair(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, const NextCounts& Nx, bool mix_first) {
-    // measured on 32 x 11.2 M: 1.085-1.088 ms at 9 two-wave workgroups per compute unit, 1.091-1.092 at 10, 1.10 at 11,
-    // 1.13 at 8 and from 12 on; 9 is also the best on 128 x 11.2 M, 32 x 25.6 M, 32 x 100 M and 64 x 6.65 M (by 0.5-1 % over 10)
+    // measured on 32 x 11.2 M (rows 1 KB aligned): 1.072 ms at 9 two-wave workgroups per compute unit, 1.074 at 10, 1.084 at 11,
+    // 1.10 at 12, 1.12 at 8, 1.13 uncapped; 9 is also the best on 128 x 11.2 M, 32 x 25.6 M, 32 x 100 M and 64 x 6.65 M (by 0.5-1 % over 10)
     const int32_t bpc = residency_for(c, 9, (uint64_t)c->ntiles * (uint64_t)A.n_units);
     uint32_t lds = residency_lds_bytes(bpc);
     if (lds > 2048u) lds -= 2048u;                     // the kernel's own 2 KB of LDS count towards the slice
@@ -736,8 +736,10 @@ saps_status saps_consensus(saps_ctx* c, const float* X, float* mean_out, double*
         return fail(c, SAPS_EINVAL, "X/mean/D null or misaligned");
     const uint32_t blocks = (uint32_t)((c->N + 4 * BLOCK - 1) / (4 * BLOCK));
     if (blocks > 0) {
-        // 3 four-wave workgroups per compute unit (8 rows in flight per lane): 6.81 against 6.62 TB/s uncapped on 32 x 11.2 M
-        const uint32_t clds = residency_lds_bytes(c->blocks_per_cu >= 0 ? c->blocks_per_cu : 3);
+        // 8 rows in flight per lane.  When the mean is written too, 3 four-wave workgroups per compute unit are 2-3 % faster
+        // than no cap (32 x 11.2 M: 0.240-0.245 against 0.247-0.251 ms over eight row strides); without it no cap is as fast
+        // or faster (0.210-0.214 against 0.213-0.221 ms)
+        const uint32_t clds = residency_lds_bytes(c->blocks_per_cu >= 0 ? c->blocks_per_cu : (mean_out ? 3 : 0));
         profile_mark(c, false);
         if (c->nontemporal) hipLaunchKernelGGL(consensus_kernel<true>, dim3(blocks), dim3(BLOCK), clds, c->stream, X, c->ld, (uint32_t)c->N, c->n, mean_out, c->d_partial);
         else hipLaunchKernelGGL(consensus_kernel<false>, dim3(blocks), dim3(BLOCK), clds, c->stream, X, c->ld, (uint32_t)c->N, c->n, mean_out, c->d_partial);

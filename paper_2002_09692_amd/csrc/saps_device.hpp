@@ -776,10 +776,15 @@ __global__ __launch_bounds__(FUSED_BLOCK) void fused_pair_kernel(MaskParams P, F
     }
     if (total) swap[wave][lane] = x;                                     // what the peer averages with (wave-uniform branch)
     if (mine && m && A.msg) {
-        uint32_t pos = pos0;
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            if ((m >> r) & 1u) A.msg[(int64_t)row * A.msg_ld + pos++] = x[r];
+        // one store per kept coordinate of the lane: almost always a single one
+        float* out = A.msg + (int64_t)row * A.msg_ld + pos0;
+        uint32_t mm = m;
+        do {
+            const uint32_t r = (uint32_t)__builtin_ctz(mm);
+            const float lo = (r & 1u) ? x[1] : x[0], hi = (r & 1u) ? x[3] : x[2];
+            *out++ = (r & 2u) ? hi : lo;
+            mm &= mm - 1u;
+        } while (mm);
     }
     __syncthreads();
     if (total && paired) {

@@ -130,7 +130,9 @@ class Workload:
     def sigma_K(self) -> float:
         return float(np.sqrt(sum(s * (1 / c) * (1 - 1 / c) for s, c in zip(self.seg_sizes, self.seg_c))))
 
-    def ld(self, align: int = 64) -> int:
+    def ld(self, align: int = 256) -> int:
+        """Row stride in floats: N rounded up to whole wave tiles of 256 coordinates (1 KB), so that every
+        row starts on a 1 KB boundary and a wave's 1 KB access never straddles one."""
         return (self.N + align - 1) // align * align
 
     B_thres: float = 50.0        # Mbps, for matching == "bandwidth"
