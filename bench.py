@@ -55,7 +55,7 @@ def cpu_model() -> str:
     return "unknown"
 
 
-def measure(name: str, steps, warm: int, cpu_rounds, tune: str, with_cpu: bool, extras: bool) -> dict:
+def measure(name: str, steps, warm: int, cpu_rounds, tune: str, with_cpu: bool, extras: bool, ld_pad: int = 0) -> dict:
     """Runs one workload: oracle-checked rounds, timed rounds on the library's default path, a second pass
     with the dominant kernel bracketed by HIP events, yardsticks.  `extras` adds the graph replay and the
     consensus diagnostics (headline only)."""
@@ -66,7 +66,7 @@ def measure(name: str, steps, warm: int, cpu_rounds, tune: str, with_cpu: bool, 
     stream = torch.cuda.current_stream()
     wl = synth.workload(name)
     steps = steps if steps is not None else wl.rounds
-    n, N, ld = wl.n, wl.N, wl.ld()
+    n, N, ld = wl.n, wl.N, wl.ld() + ld_pad
     cap = synth.recommended_capacity(wl)
     seed = 0
 
@@ -350,6 +350,8 @@ def main() -> int:
     ap.add_argument("--cpu-rounds", type=int, default=None)
     ap.add_argument("--no-others", action="store_true", help="measure the headline workload only")
     ap.add_argument("--tune", default="", help="comma list knob=value, e.g. ppb=8,xcd=1,nt=1,path=1")
+    ap.add_argument("--ld-pad", type=int, default=0, help="floats added to the row stride (multiple of 4; for layout sweeps: "
+                                                          "the default stride is N rounded up to 256 floats)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build keeps all n worker replicas in the HBM of ONE GPU; there is no multi-GPU path "
@@ -367,7 +369,10 @@ def main() -> int:
     stream = torch.cuda.Stream()
     torch.cuda.set_stream(stream)
 
-    m = measure(args.workload, args.steps, args.warmup, args.cpu_rounds, args.tune, not args.no_cpu, extras=True)
+    if args.ld_pad < 0 or args.ld_pad % 4:
+        print("bench.py: --ld-pad must be a non-negative multiple of 4", file=sys.stderr)
+        return 2
+    m = measure(args.workload, args.steps, args.warmup, args.cpu_rounds, args.tune, not args.no_cpu, extras=True, ld_pad=args.ld_pad)
 
     # measured HBM bytes per launch of the dominant kernel (rocprofv3 FETCH_SIZE / WRITE_SIZE runs of this same
     # command, scaled by the copy kernel of known size; written by paper_2002_09692_amd/traffic.py together
@@ -387,7 +392,7 @@ def main() -> int:
                     "this tree; re-run the rocprofv3 --pmc passes and paper_2002_09692_amd/traffic.py")
 
     others = None
-    if args.workload == "cfg3" and not args.no_others and not args.tune:
+    if args.workload == "cfg3" and not args.no_others and not args.tune and not args.ld_pad:
         others = {}
         for name in ALL_WORKLOADS:
             if name == args.workload:

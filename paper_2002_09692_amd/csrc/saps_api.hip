@@ -326,8 +326,9 @@ void launch_fused_nt(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const
 // K7p: one row per wave, one pair per workgroup (update rounds only).
 template <int MODE>
 void launch_fused_pair(saps_ctx* c, const MaskParams& P, const FusedArgs& A, const Units& U, const NextCounts& Nx, bool mix_first) {
-    // measured on 32 x 11.2 M (rows 1 KB aligned): 1.072 ms at 9 two-wave workgroups per compute unit, 1.074 at 10, 1.084 at 11,
-    // 1.10 at 12, 1.12 at 8, 1.13 uncapped; 9 is also the best on 128 x 11.2 M, 32 x 25.6 M, 32 x 100 M and 64 x 6.65 M (by 0.5-1 % over 10)
+    // measured on 32 x 11.2 M (rows 1 KB aligned, kernel trace on one box): 1.065 ms at 9 two-wave workgroups per compute unit,
+    // 1.067 at 10, 1.074 at 11, 1.086 at 12 and uncapped, 1.107 at 8; 9 is also the best on 128 x 11.2 M, 32 x 25.6 M,
+    // 32 x 100 M and 64 x 6.65 M (by 0.5-1 % over 10)
     const int32_t bpc = residency_for(c, 9, (uint64_t)c->ntiles * (uint64_t)A.n_units);
     uint32_t lds = residency_lds_bytes(bpc);
     if (lds > 2048u) lds -= 2048u;                     // the kernel's own 2 KB of LDS count towards the slice
