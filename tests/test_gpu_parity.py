@@ -802,3 +802,44 @@ def test_fused_round_both_wave_shapes(B, n, N, ld, c, rpw, with_v):
     peer = rand_peer(n, n + N, singles=1 if n > 2 else 0)
     r = run_round_both(B, n, N, ld, c, None, 5, 3, peer, fused=True, with_v=with_v, tuning=[(B.TUNE_ROW_PER_WAVE, rpw)])
     check_round(r, N)
+
+
+@pytest.mark.parametrize("bpc", [-1, 0, 3, 5, 9, 13, 16, 21, 32])
+def test_residency_knob_changes_no_result(B, bpc):
+    """The resident-workgroups knob only sizes a never-touched LDS slice: every admitted value must launch
+    (a slice that the hardware refuses would surface as a HIP error) and give the oracle's bits, in every
+    kernel that honours it: the three shapes of the update round, the local step, the consensus kernel."""
+    n, N, ld, c = 6, 70_001, 70_144, 50.0
+    peer = rand_peer(n, 11)
+    for rpw in (0, 1, 2):
+        for with_v in (True, False):
+            r = run_round_both(B, n, N, ld, c, None, 9, 4, peer, fused=True, with_v=with_v,
+                               tuning=[(B.TUNE_ROW_PER_WAVE, rpw), (B.TUNE_BLOCKS_PER_CU, bpc)])
+            check_round(r, N)
+    X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2); V0 = rand_models(n, N, ld, 3)
+    for with_v in (True, False):
+        Xo, Vo = X0.copy(), V0.copy()
+        assert O.sgd_step(Xo, G0, Vo if with_v else None, 0.1, 0.9 if with_v else 0.0, N=N) == O.OK
+        X, G, V = dev(X0), dev(G0), dev(V0)
+        mean = torch.zeros(N, device="cuda"); D = torch.zeros(2, dtype=torch.float64, device="cuda")
+        with B.SapsContext(n, N, ld, 0) as ctx:
+            ctx.saps_set_tuning(B.TUNE_BLOCKS_PER_CU, bpc)
+            ctx.saps_sgd_step(X, G, V if with_v else None, 0.1, 0.9 if with_v else 0.0)
+            ctx.saps_consensus(X, mean, D[0:1])
+            ctx.saps_consensus(X, None, D[1:2])
+            assert ctx.saps_poll_status()[0] == 0
+        assert_bits(X.cpu().numpy(), Xo, "X after the local step")
+        if with_v:
+            assert_bits(V.cpu().numpy(), Vo, "V after the local step")
+        m_o, D_o = O.consensus(Xo, N)
+        assert np.array_equal(mean.cpu().numpy().view(np.uint32), m_o.view(np.uint32))
+        d = D.cpu().numpy()
+        assert d[0] == d[1] and abs(d[0] - D_o) <= 1e-10 * max(D_o, 1e-30)
+
+
+def test_residency_knob_rejects_values_outside_its_range(B):
+    with B.SapsContext(2, 1000, 1024, 64) as ctx:
+        for bad in (-2, 1, 2, 33, 1000):
+            assert ctx.saps_set_tuning(B.TUNE_BLOCKS_PER_CU, bad, check=False) == B.EINVAL
+        for good in (-1, 0, 3, 32):
+            assert ctx.saps_set_tuning(B.TUNE_BLOCKS_PER_CU, good, check=False) == 0
