@@ -843,3 +843,34 @@ def test_residency_knob_rejects_values_outside_its_range(B):
             assert ctx.saps_set_tuning(B.TUNE_BLOCKS_PER_CU, bad, check=False) == B.EINVAL
         for good in (-1, 0, 3, 32):
             assert ctx.saps_set_tuning(B.TUNE_BLOCKS_PER_CU, good, check=False) == 0
+
+
+@pytest.mark.parametrize("n,N,ld,c", [(4, 100_000, 100_032, 100.0), (5, 4097, 4100, 2.0), (6, 70_001, 70_144, 8.0), (3, 5, 8, 1.0)])
+@pytest.mark.parametrize("xcd,nt", [(1, 1), (0, 0), (1, 0)])
+def test_xcd_remap_and_plain_access_knobs_change_no_result(B, n, N, ld, c, xcd, nt):
+    """Tile ranges per XCD (a permutation of the workgroups, with idle ones when the count is no multiple of 8) and
+    plain instead of streaming accesses: same bits in the update round (both row orders), the tile walk, the list
+    exchange, the local step and the copy."""
+    tuning = [(B.TUNE_XCD_REMAP, xcd), (B.TUNE_NONTEMPORAL, nt)]
+    peer = rand_peer(n, 3 * n + xcd, singles=1 if n % 2 else 0)
+    for with_v in (True, False):
+        for ppb in (1, 4):
+            r = run_round_both(B, n, N, ld, c, None, 6, 2, peer, fused=True, with_v=with_v,
+                               tuning=tuning + [(B.TUNE_PAIRS_PER_BLOCK, ppb)])
+            check_round(r, N)
+    for path in (1, 2):
+        r = run_round_both(B, n, N, ld, c, None, 6, 2, peer, fused=False, tuning=tuning + [(B.TUNE_EXCHANGE_PATH, path)])
+        check_round(r, N)
+    X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2); V0 = rand_models(n, N, ld, 3)
+    Xo, Vo = X0.copy(), V0.copy()
+    assert O.sgd_step(Xo, G0, Vo, 0.1, 0.9, N=N) == O.OK
+    X, G, V = dev(X0), dev(G0), dev(V0)
+    dst = torch.zeros_like(X)
+    with B.SapsContext(n, N, ld, 0) as ctx:
+        for k, v in tuning:
+            ctx.saps_set_tuning(k, v)
+        ctx.saps_sgd_step(X, G, V, 0.1, 0.9)
+        ctx.saps_stream_copy(dst, X)
+        assert ctx.saps_poll_status()[0] == 0
+    assert_bits(X.cpu().numpy(), Xo, "X"); assert_bits(V.cpu().numpy(), Vo, "V")
+    assert_bits(dst.cpu().numpy(), X.cpu().numpy(), "copy")
