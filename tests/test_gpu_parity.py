@@ -874,3 +874,28 @@ def test_xcd_remap_and_plain_access_knobs_change_no_result(B, n, N, ld, c, xcd, 
         assert ctx.saps_poll_status()[0] == 0
     assert_bits(X.cpu().numpy(), Xo, "X"); assert_bits(V.cpu().numpy(), Vo, "V")
     assert_bits(dst.cpu().numpy(), X.cpu().numpy(), "copy")
+
+
+def test_unfused_compact_and_merge_with_both_store_policies(B):
+    """saps_mask_compact + saps_merge on a layout whose touched lines fit the caches (write-back scatter) and on
+    one far beyond (streaming scatter): idx, msg and X as the oracle's, with an unmatched worker."""
+    for n, N, c in ((5, 300_000, 50.0), (65, 2_500_000, 20.0)):
+        ld = (N + 255) // 256 * 256
+        cap = int(N / c * 1.2) // 4 * 4
+        X0 = rand_models(n, N, ld, 21)
+        peer = rand_peer(n, 8, singles=1)
+        Xo = X0.copy()
+        rc, K, idx_o, msg_o = O.mask_compact(Xo, N, 77, 5, c, msg_ld=cap)
+        assert rc == O.OK
+        assert O.merge(Xo, N, peer, idx_o, msg_o, K) == O.OK
+        X = dev(X0)
+        idx = torch.full((cap,), -1, dtype=torch.int32, device="cuda"); msg = torch.full((n, cap), -5.0, device="cuda")
+        Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+        with B.SapsContext(n, N, ld, cap, c) as ctx:
+            ctx.saps_mask_compact(X, 77, 5, idx, msg, Kd)
+            ctx.saps_merge(X, peer, idx, msg, Kd)
+            assert ctx.saps_poll_status() == (0, K)
+        assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K])
+        assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], "msg")
+        assert np.all(msg.cpu().numpy()[:, K:] == -5.0)
+        assert_bits(X.cpu().numpy(), Xo, f"X (n={n})")
