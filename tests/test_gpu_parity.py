@@ -899,3 +899,61 @@ def test_unfused_compact_and_merge_with_both_store_policies(B):
         assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], "msg")
         assert np.all(msg.cpu().numpy()[:, K:] == -5.0)
         assert_bits(X.cpu().numpy(), Xo, f"X (n={n})")
+
+
+@pytest.mark.parametrize("rpw,ppb,nt", [(0, 1, 1), (0, 4, 1), (0, 8, 0), (1, 1, 0), (2, 1, 1), (2, 1, 0)])
+@pytest.mark.parametrize("with_v", [True, False])
+def test_mix_then_step_in_every_kernel_shape(B, rpw, ppb, nt, with_v):
+    """The mix-then-step order (Eq. (7)) in every shape of the update round: both rows per wave with 1, 4 or 8
+    units per workgroup, one row per wave, plain and streaming accesses, with an unmatched worker."""
+    n, N, ld, c = 7, 33_333, 33_536, 6.0
+    peer = rand_peer(n, 41, singles=1)
+    msg_ld = (int(N / c * 1.3) + 64) // 4 * 4
+    X0 = rand_models(n, N, ld, 1); G0 = rand_models(n, N, ld, 2, pad=555.0, scale=1e-3)
+    V0 = rand_models(n, N, ld, 3, pad=333.0, scale=1e-3) if with_v else None
+    mu = 0.9 if with_v else 0.0
+    Xo = X0.copy(); Vo = None if V0 is None else V0.copy()
+    rc, K, idx_o, msg_o = O.round_(Xo, G0, Vo, N, 0.1, mu, 5, 3, peer, c, msg_ld=msg_ld, mix_first=True)
+    assert rc == O.OK
+    X, G = dev(X0), dev(G0); V = None if V0 is None else dev(V0)
+    idx = torch.full((msg_ld,), -1, dtype=torch.int32, device="cuda")
+    msg = torch.full((n, msg_ld), -5.0, device="cuda"); Kd = torch.zeros(1, dtype=torch.int64, device="cuda")
+    with B.SapsContext(n, N, ld, msg_ld, c) as ctx:
+        for k, v in ((B.TUNE_ROW_PER_WAVE, rpw), (B.TUNE_PAIRS_PER_BLOCK, ppb), (B.TUNE_NONTEMPORAL, nt)):
+            ctx.saps_set_tuning(k, v)
+        ctx.saps_round_ex(X, G, V, 0.1, mu, 5, 3, peer, idx, msg, Kd, flags=B.ROUND_MIX_THEN_STEP)
+        assert ctx.saps_poll_status() == (0, K)
+    assert np.array_equal(idx.cpu().numpy().view(np.uint32)[:K], idx_o[:K])
+    assert_bits(msg.cpu().numpy()[:, :K], msg_o[:, :K], "msg")
+    assert np.all(msg.cpu().numpy()[:, K:] == -5.0)
+    assert_bits(X.cpu().numpy(), Xo, "X")
+    if with_v:
+        assert_bits(V.cpu().numpy(), Vo, "V")
+
+
+def test_hybrid_exchange_with_streaming_scatter(B):
+    """Path 3 on a mixed-ratio layout whose touched lines exceed the caches: dense tiles are walked, the list
+    kernel skips them and scatters with streaming stores."""
+    n = 64
+    sizes = [300_001, 700_003, 499_996, 1_000_000]
+    cs = [4.0, 100.0, 8.0, 1000.0]
+    off = np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+    N = int(off[-1]); ld = (N + 255) // 256 * 256
+    cap = (int(sum(s / c for s, c in zip(sizes, cs)) * 1.1) + 256) // 4 * 4
+    for path in (3, 1):
+        r = run_round_both(B, n, N, ld, cs, off, 13, 6, rand_peer(n, 9), fused=False, msg_ld=cap,
+                           tuning=[(B.TUNE_EXCHANGE_PATH, path)])
+        check_round(r, N)
+
+
+def test_consensus_with_plain_loads(B):
+    n, N, ld = 9, 50_001, 50_176
+    X0 = rand_models(n, N, ld, 4)
+    m_o, D_o = O.consensus(X0, N)
+    X = dev(X0); mean = torch.zeros(N, device="cuda"); D = torch.zeros(1, dtype=torch.float64, device="cuda")
+    with B.SapsContext(n, N, ld, 0) as ctx:
+        ctx.saps_set_tuning(B.TUNE_NONTEMPORAL, 0)
+        ctx.saps_consensus(X, mean, D)
+        assert ctx.saps_poll_status()[0] == 0
+    assert np.array_equal(mean.cpu().numpy().view(np.uint32), m_o.view(np.uint32))
+    assert abs(float(D.item()) - D_o) <= 1e-10 * max(D_o, 1e-30)
