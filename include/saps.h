@@ -170,7 +170,7 @@ enum {
     SAPS_TUNE_NONTEMPORAL = 2,     /* fused round and local step: 0 = plain, 1 = non-temporal loads/stores */
     SAPS_TUNE_EXCHANGE_PATH = 3,   /* exchange-only round: 0 = built-in choice by expected density, 1 = index list, 2 = tile walk,
                                       3 = index list, but whole tiles that keep at least every 12th coordinate are streamed */
-    SAPS_TUNE_BLOCKS_PER_CU = 4,   /* fused round, local step, consensus: resident workgroups per compute unit, 3..32 (rounded up to the next
+    SAPS_TUNE_BLOCKS_PER_CU = 4,   /* fused round, list exchange, local step, consensus: resident workgroups per compute unit, 3..32 (rounded up to the next
                                       count that the LDS granules admit: 1..12, 14, 16, 18, 21, 25, 32), 0 = no limit, -1 = built-in
                                       choice (a measured cap per kernel for long grids, no limit for short ones) */
     SAPS_TUNE_PREPARE_NEXT = 5,    /* saps_round: 1 (default) = the kernels of round t also count the kept coordinates of round t + 1, 0 = never */

@@ -420,16 +420,19 @@ saps_status round_impl(saps_ctx* c, float* X, const float* G, float* V, float lr
                                c->d_walk_tiles, c->n_walk, msg, c->msg_ld);
         }
         const dim3 lgrid(list_grid_x(c), (uint32_t)n_units);
+        // long grids only: 4 four-wave workgroups per compute unit (128 x 11.2 M, mixed ratios: 0.505 against 0.511 ms uncapped,
+        // 0.508 at 3, 0.511 at 6); the short grid of 32 x 25.6 M at c = 1000 loses 4 % under any cap and falls under the rule
+        const uint32_t llds = residency_lds_bytes(residency_for(c, 4, (uint64_t)lgrid.x * lgrid.y));
         if (hybrid) {
             if (c->stream_scatter)
-                hipLaunchKernelGGL((exchange_list_kernel<true, true>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
+                hipLaunchKernelGGL((exchange_list_kernel<true, true>), lgrid, dim3(BLOCK), llds, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
             else
-                hipLaunchKernelGGL((exchange_list_kernel<false, true>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
+                hipLaunchKernelGGL((exchange_list_kernel<false, true>), lgrid, dim3(BLOCK), llds, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
         } else {
             if (c->stream_scatter)
-                hipLaunchKernelGGL((exchange_list_kernel<true, false>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
+                hipLaunchKernelGGL((exchange_list_kernel<true, false>), lgrid, dim3(BLOCK), llds, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
             else
-                hipLaunchKernelGGL((exchange_list_kernel<false, false>), lgrid, dim3(BLOCK), 0, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
+                hipLaunchKernelGGL((exchange_list_kernel<false, false>), lgrid, dim3(BLOCK), llds, c->stream, X, c->ld, U, list, c->d_K, c->msg_ld, msg, c->msg_ld, c->d_walk_bits, P, c->ntiles, Nx);
         }
         profile_mark(c, true);
     }
