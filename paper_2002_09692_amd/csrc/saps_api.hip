@@ -812,13 +812,15 @@ saps_status saps_list_probe(saps_ctx* c, float* X, const uint32_t* idx, const in
     if (c->N == 0) return SAPS_OK;
     const dim3 grid(list_grid_x(c), (uint32_t)c->n);
     uint32_t* sink = reinterpret_cast<uint32_t*>(c->d_partial);
+    // the in-place variant runs at the residency of the exchange kernel whose yardstick it is
+    const uint32_t lds = write_back ? residency_lds_bytes(residency_for(c, 4, (uint64_t)grid.x * grid.y)) : 0u;
     profile_mark(c, false);
     if (!write_back)
         hipLaunchKernelGGL((list_probe_kernel<false, false>), grid, dim3(BLOCK), 0, c->stream, X, c->ld, idx, K_dev, c->msg_ld, (uint32_t)c->N, sink);
     else if (c->stream_scatter)
-        hipLaunchKernelGGL((list_probe_kernel<true, true>), grid, dim3(BLOCK), 0, c->stream, X, c->ld, idx, K_dev, c->msg_ld, (uint32_t)c->N, sink);
+        hipLaunchKernelGGL((list_probe_kernel<true, true>), grid, dim3(BLOCK), lds, c->stream, X, c->ld, idx, K_dev, c->msg_ld, (uint32_t)c->N, sink);
     else
-        hipLaunchKernelGGL((list_probe_kernel<true, false>), grid, dim3(BLOCK), 0, c->stream, X, c->ld, idx, K_dev, c->msg_ld, (uint32_t)c->N, sink);
+        hipLaunchKernelGGL((list_probe_kernel<true, false>), grid, dim3(BLOCK), lds, c->stream, X, c->ld, idx, K_dev, c->msg_ld, (uint32_t)c->N, sink);
     profile_mark(c, true);
     SAPS_HIP(c, hipGetLastError());
     return SAPS_OK;
